@@ -1,0 +1,148 @@
+/*
+ * LAWCAT sequence-mixing oracle: plain, slow, fp64, token by token.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the independent checker for the HIP
+ * library; it shares no code with it and must never be called from the product
+ * path.  Only the tests, the smoke check and the benchmark's cpu_baseline leg
+ * may load it.
+ *
+ * What it computes (paper section 4):
+ *   - section 4.1: causal depthwise Conv1D across tokens, kernel size r+1,
+ *       x~_t = sum_{delta=0..r} w_delta * x_{t-delta}   (the "simplest case" sum)
+ *     followed by an optional pointwise positive map (1+ELU, named in section 2
+ *     as an example of phi).
+ *   - section 4.2, KV-state update equation (first equation of 4.2):
+ *       S_t = G_t (.) S_{t-1} + k_t^T v_t ,  S_0 = 0 unless a start state is given
+ *     with the gate per key channel (G_t = alpha_t^T 1), alpha_t = sigmoid(g_t)^gate_scale,
+ *   - section 4.2, normalized output equation (last equation of 4.2):
+ *       o_t = q_t S_t / (q_t . z_t + eps) ,  z_t = alpha_t (.) z_{t-1} + k_t
+ *     (z_t is the paper's "k^T times 1_{1 x dv}, gated, then mean over dv": with a
+ *     per-channel gate all dv columns are identical, so the mean is that column).
+ *
+ * Every function below is the definition written out: no blocking, no fusion.
+ * Pinned by tests/test_oracle_pins.py (brute-force quadratic form, closed forms,
+ * invariants); nothing here is "parity unpinned".
+ *
+ * Build: gcc -O2 -fopenmp -shared -fPIC -o liblawcat_oracle.so lawcat_oracle.c -lm
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* phi: 0 = identity, 1 = 1+ELU (x>0 ? 1+x : exp(x)); section 2, kernel-based linear attention. */
+static double feature_map(double x, int kind) {
+  if (kind == 1) return x > 0.0 ? 1.0 + x : exp(x);
+  return x;
+}
+
+/* log(sigmoid(g)), stable on both tails; the gate of section 4.2 is a sigmoid. */
+static double log_sigmoid(double g) {
+  return g < 0.0 ? g - log1p(exp(g)) : -log1p(exp(-g));
+}
+
+/*
+ * Section 4.1 direct sum.  x: [B,T,H,d]; w: [H,d,W] with w[..,delta] multiplying x[t-delta];
+ * halo: NULL (zeros before the first token) or [B,W-1,H,d], oldest row first, holding
+ * the W-1 raw rows that precede x (the "cache limited by the kernel size" of 4.1).
+ * y: [B,T,H,d] = phi(conv).
+ */
+void lawcat_oracle_conv1d_causal(int B, int T, int H, int d, int W, const double* x,
+                                 const double* w, const double* halo, int phi, double* y) {
+  for (int b = 0; b < B; ++b)
+    for (int t = 0; t < T; ++t)
+      for (int h = 0; h < H; ++h)
+        for (int c = 0; c < d; ++c) {
+          double acc = 0.0;
+          for (int delta = 0; delta < W; ++delta) {
+            int s = t - delta; /* source token */
+            double xv;
+            if (s >= 0) {
+              xv = x[(((size_t)b * T + s) * H + h) * d + c];
+            } else if (halo != NULL) {
+              int r = (W - 1) + s; /* s = -1 is the newest halo row, index W-2 */
+              xv = halo[(((size_t)b * (W - 1) + r) * H + h) * d + c];
+            } else {
+              xv = 0.0;
+            }
+            acc += w[((size_t)h * d + c) * W + delta] * xv;
+          }
+          y[(((size_t)b * T + t) * H + h) * d + c] = feature_map(acc, phi);
+        }
+}
+
+/*
+ * Section 4.2 recurrence, token by token.
+ *   q: [B,T,Hq,dk]  k,g: [B,T,Hkv,dk]  v: [B,T,Hkv,dv]   (q, k are already q-dot, k-dot)
+ *   S0: NULL or [B,Hkv,dk,dv];  z0: NULL or [B,Hkv,dk]
+ *   o: [B,T,Hq,dv]  den: [B,T,Hq] (q.z + eps)  num: NULL or [B,T,Hq,dv] (q S, before the division)
+ *   S_out: [B,Hkv,dk,dv]  z_out: [B,Hkv,dk]
+ * Query head h uses the state of kv head h / (Hq/Hkv).
+ */
+void lawcat_oracle_gla_prefill(int B, int T, int Hq, int Hkv, int dk, int dv, const double* q,
+                               const double* k, const double* v, const double* g,
+                               double gate_scale, double eps, const double* S0, const double* z0,
+                               double* o, double* den, double* num, double* S_out,
+                               double* z_out) {
+  const int group = Hq / Hkv;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int b = 0; b < B; ++b)
+    for (int hk = 0; hk < Hkv; ++hk) {
+      double* S = (double*)malloc(sizeof(double) * (size_t)dk * dv);
+      double* z = (double*)malloc(sizeof(double) * (size_t)dk);
+      double* alpha = (double*)malloc(sizeof(double) * (size_t)dk);
+      const size_t sidx = ((size_t)b * Hkv + hk);
+      for (int c = 0; c < dk; ++c) {
+        z[c] = z0 ? z0[sidx * dk + c] : 0.0;
+        for (int j = 0; j < dv; ++j) S[(size_t)c * dv + j] = S0 ? S0[(sidx * dk + c) * dv + j] : 0.0;
+      }
+      for (int t = 0; t < T; ++t) {
+        const double* kt = k + (((size_t)b * T + t) * Hkv + hk) * dk;
+        const double* gt = g + (((size_t)b * T + t) * Hkv + hk) * dk;
+        const double* vt = v + (((size_t)b * T + t) * Hkv + hk) * dv;
+        for (int c = 0; c < dk; ++c) alpha[c] = exp(gate_scale * log_sigmoid(gt[c]));
+        /* S_t = G_t (.) S_{t-1} + k_t^T v_t ; z_t = alpha_t (.) z_{t-1} + k_t */
+        for (int c = 0; c < dk; ++c) {
+          double* Sc = S + (size_t)c * dv;
+          for (int j = 0; j < dv; ++j) Sc[j] = alpha[c] * Sc[j] + kt[c] * vt[j];
+          z[c] = alpha[c] * z[c] + kt[c];
+        }
+        /* o_t = q_t S_t / (q_t . z_t + eps) for every query head of the group */
+        for (int r = 0; r < group; ++r) {
+          const int hq = hk * group + r;
+          const double* qt = q + (((size_t)b * T + t) * Hq + hq) * dk;
+          double* ot = o + (((size_t)b * T + t) * Hq + hq) * dv;
+          double dsum = 0.0;
+          for (int c = 0; c < dk; ++c) dsum += qt[c] * z[c];
+          dsum += eps;
+          den[((size_t)b * T + t) * Hq + hq] = dsum;
+          for (int j = 0; j < dv; ++j) ot[j] = 0.0;
+          for (int c = 0; c < dk; ++c) {
+            const double* Sc = S + (size_t)c * dv;
+            for (int j = 0; j < dv; ++j) ot[j] += qt[c] * Sc[j];
+          }
+          if (num) {
+            double* nt = num + (((size_t)b * T + t) * Hq + hq) * dv;
+            for (int j = 0; j < dv; ++j) nt[j] = ot[j];
+          }
+          for (int j = 0; j < dv; ++j) ot[j] = ot[j] / dsum;
+        }
+      }
+      for (int c = 0; c < dk; ++c) {
+        z_out[sidx * dk + c] = z[c];
+        for (int j = 0; j < dv; ++j) S_out[(sidx * dk + c) * dv + j] = S[(size_t)c * dv + j];
+      }
+      free(S);
+      free(z);
+      free(alpha);
+    }
+}
+
+int lawcat_oracle_max_threads(void) {
+#ifdef _OPENMP
+  extern int omp_get_max_threads(void);
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

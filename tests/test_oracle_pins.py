@@ -1,0 +1,332 @@
+"""Pins for the fp64 oracle: each test checks it against something other than itself --
+the quadratic (all-pairs) form of the paper's last two equations of section 4.2, closed
+forms, special cases that reduce to textbook routines, and invariants.  CPU only."""
+import os
+
+import numpy as np
+import pytest
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand(rng, *shape):
+    return rng.standard_normal(shape)
+
+
+def _logsig(g):
+    return -np.logaddexp(0.0, -g)
+
+
+def brute_force_quadratic(q, k, v, g, gate_scale=1.0):
+    """All-pairs form (section 4.2, state sum over J_{i,t} and the normalized output):
+    P[t,i] = sum_c q[t,c] k[i,c] prod_{s=i+1..t} alpha[s,c],  o = (P V) / (P 1).
+    Single head: q,k,g [T,dk], v [T,dv].  J_{t,t} = 1 (empty product)."""
+    T = q.shape[0]
+    alpha = np.exp(gate_scale * _logsig(g))
+    P = np.zeros((T, T))
+    for t in range(T):
+        for i in range(t + 1):
+            J = np.ones(q.shape[1])
+            for s in range(i + 1, t + 1):
+                J = J * alpha[s]
+            P[t, i] = np.sum(q[t] * k[i] * J)
+    num = P @ v
+    den = P.sum(axis=1)
+    return num / den[:, None], num, den
+
+
+def test_hand_example_fixture(oracle):
+    rows = np.loadtxt(os.path.join(GOLDEN, "hand_example_d1.txt"))
+    v = np.array([1.0, 2.0, 3.0]).reshape(1, 3, 1, 1)
+    one = np.ones((1, 3, 1, 1))
+    r = oracle.gla_prefill(one, one, v, np.zeros((1, 3, 1, 1)))
+    np.testing.assert_allclose(r["num"].ravel(), rows[:, 1], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(r["den"].ravel(), rows[:, 2], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(r["o"].ravel(), rows[:, 3], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(r["S"].ravel(), [4.25], atol=1e-15)
+    np.testing.assert_allclose(r["z"].ravel(), [1.75], atol=1e-15)
+
+
+@pytest.mark.parametrize("T,dk,dv,scale", [(1, 3, 2, 1.0), (7, 4, 5, 1.0), (40, 8, 6, 0.25)])
+def test_matches_brute_force_quadratic(oracle, T, dk, dv, scale):
+    rng = np.random.default_rng(T)
+    q, k, g, v = _rand(rng, T, dk), _rand(rng, T, dk), _rand(rng, T, dk), _rand(rng, T, dv)
+    o_ref, num_ref, den_ref = brute_force_quadratic(q, k, v, g, scale)
+    r = oracle.gla_prefill(q[None, :, None], k[None, :, None], v[None, :, None], g[None, :, None], scale)
+    np.testing.assert_allclose(r["num"][0, :, 0], num_ref, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(r["den"][0, :, 0], den_ref, rtol=1e-11, atol=1e-12)
+    ok = np.abs(den_ref) > 1e-3
+    np.testing.assert_allclose(r["o"][0, ok, 0], o_ref[ok], rtol=1e-8, atol=1e-9)
+
+
+def test_gqa_heads_share_kv_state(oracle):
+    """Query head h reads the state of kv head h // (Hq/Hkv): compare with per-head runs."""
+    rng = np.random.default_rng(5)
+    B, T, Hq, Hkv, dk, dv = 2, 9, 6, 2, 4, 3
+    q, k = _rand(rng, B, T, Hq, dk), _rand(rng, B, T, Hkv, dk)
+    v, g = _rand(rng, B, T, Hkv, dv), _rand(rng, B, T, Hkv, dk)
+    r = oracle.gla_prefill(q, k, v, g)
+    for b in range(B):
+        for h in range(Hq):
+            hk = h // (Hq // Hkv)
+            _, num, den = brute_force_quadratic(q[b, :, h], k[b, :, hk], v[b, :, hk], g[b, :, hk])
+            np.testing.assert_allclose(r["num"][b, :, h], num, rtol=1e-11, atol=1e-12)
+            np.testing.assert_allclose(r["den"][b, :, h], den, rtol=1e-11, atol=1e-12)
+
+
+def test_gates_one_is_cumsum_linear_attention(oracle):
+    """Gate -> 1 reduces to the kernel linear attention of section 2 (prefix sums)."""
+    rng = np.random.default_rng(1)
+    T, dk, dv = 33, 5, 4
+    q, k = np.abs(_rand(rng, T, dk)) + 0.1, np.abs(_rand(rng, T, dk)) + 0.1
+    v = _rand(rng, T, dv)
+    g = np.full((T, dk), 800.0)  # sigmoid = 1 exactly in fp64
+    r = oracle.gla_prefill(q[None, :, None], k[None, :, None], v[None, :, None], g[None, :, None])
+    kv = np.cumsum(k[:, :, None] * v[:, None, :], axis=0)
+    ksum = np.cumsum(k, axis=0)
+    o_ref = np.einsum("tc,tcj->tj", q, kv) / np.einsum("tc,tc->t", q, ksum)[:, None]
+    np.testing.assert_allclose(r["o"][0, :, 0], o_ref, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(r["S"][0, 0], kv[-1], rtol=1e-12)
+    np.testing.assert_allclose(r["z"][0, 0], ksum[-1], rtol=1e-12)
+
+
+def test_gates_zero_returns_current_value(oracle):
+    """Gate -> 0 wipes the history each step: S_t = k_t^T v_t, so o_t = v_t."""
+    rng = np.random.default_rng(2)
+    T, dk, dv = 12, 4, 3
+    q, k, v = _rand(rng, T, dk), _rand(rng, T, dk), _rand(rng, T, dv)
+    g = np.full((T, dk), -800.0)
+    r = oracle.gla_prefill(q[None, :, None], k[None, :, None], v[None, :, None], g[None, :, None])
+    np.testing.assert_allclose(r["o"][0, :, 0], v, rtol=1e-12, atol=1e-13)
+
+
+def test_geometric_closed_form(oracle):
+    """Constant scalar gate a and constant k: z_t = k (1-a^t)/(1-a); S_t likewise with constant v."""
+    T, dk, dv = 20, 3, 2
+    a = 0.7
+    gl = np.log(a / (1 - a))  # sigmoid(gl) = a
+    k = np.array([0.5, -1.0, 2.0])
+    v = np.array([3.0, -4.0])
+    q = np.array([1.0, 0.25, 0.5])
+    ones = np.ones((1, T, 1, 1))
+    r = oracle.gla_prefill(q * ones, k * ones, v * ones, gl * np.ones((1, T, 1, dk)))
+    geo = (1 - a ** T) / (1 - a)
+    np.testing.assert_allclose(r["z"][0, 0], k * geo, rtol=1e-13)
+    np.testing.assert_allclose(r["S"][0, 0], np.outer(k, v) * geo, rtol=1e-13)
+    t = np.arange(1, T + 1)
+    np.testing.assert_allclose(r["den"][0, :, 0], (q @ k) * (1 - a ** t) / (1 - a), rtol=1e-13)
+
+
+def test_gate_scale_is_a_power_of_the_gate(oracle):
+    """alpha = sigmoid(g)^gate_scale: scale 2 on a one-step decay squares it."""
+    q = np.ones((1, 2, 1, 1))
+    v = np.array([1.0, 0.0]).reshape(1, 2, 1, 1)
+    g = np.array([0.3, -0.4]).reshape(1, 2, 1, 1)
+    sig = 1 / (1 + np.exp(0.4))
+    for s in (1.0, 2.0, 0.0625):
+        r = oracle.gla_prefill(q, q, v, g, gate_scale=s)
+        np.testing.assert_allclose(r["S"].ravel(), [sig ** s], rtol=1e-14)
+
+
+def test_constant_v_and_shift_equivariance(oracle):
+    """Weights sum to one: constant v gives that constant; o(V + c) = o(V) + c."""
+    rng = np.random.default_rng(3)
+    B, T, Hq, Hkv, dk, dv = 1, 25, 4, 2, 6, 5
+    q, k = _rand(rng, B, T, Hq, dk), _rand(rng, B, T, Hkv, dk)
+    g, v = _rand(rng, B, T, Hkv, dk), _rand(rng, B, T, Hkv, dv)
+    c = np.array([0.5, -2.0, 3.0, 0.0, 1.0])
+    r0 = oracle.gla_prefill(q, k, v, g)
+    ok = np.abs(r0["den"]) > 1e-2
+    r1 = oracle.gla_prefill(q, k, v + c, g)
+    np.testing.assert_allclose(r1["o"][ok], r0["o"][ok] + c, rtol=1e-8, atol=1e-8)
+    r2 = oracle.gla_prefill(q, k, np.broadcast_to(c, v.shape), g)
+    np.testing.assert_allclose(r2["o"][ok], np.broadcast_to(c, r2["o"].shape)[ok], rtol=1e-8, atol=1e-8)
+
+
+def test_convex_hull_with_positive_features(oracle):
+    rng = np.random.default_rng(4)
+    T, dk, dv = 50, 8, 4
+    q, k = np.exp(_rand(rng, T, dk)), np.exp(_rand(rng, T, dk))
+    g, v = _rand(rng, T, dk), _rand(rng, T, dv)
+    r = oracle.gla_prefill(q[None, :, None], k[None, :, None], v[None, :, None], g[None, :, None])
+    o = r["o"][0, :, 0]
+    lo, hi = np.minimum.accumulate(v, axis=0), np.maximum.accumulate(v, axis=0)
+    assert np.all(o >= lo - 1e-12) and np.all(o <= hi + 1e-12)
+    assert np.all(r["den"] > 0)
+
+
+def test_scale_invariance(oracle):
+    """A scalar on q (even per token) or a global scalar on k cancels in the normalized output."""
+    rng = np.random.default_rng(6)
+    T, dk, dv = 30, 6, 4
+    q, k = np.exp(_rand(rng, T, dk)), np.exp(_rand(rng, T, dk))
+    g, v = _rand(rng, T, dk), _rand(rng, T, dv)
+    f = lambda q_, k_: oracle.gla_prefill(q_[None, :, None], k_[None, :, None], v[None, :, None], g[None, :, None])["o"]
+    base = f(q, k)
+    s = np.exp(_rand(rng, T, 1))
+    np.testing.assert_allclose(f(q * s, k), base, rtol=1e-12)
+    np.testing.assert_allclose(f(q, k * 3.7), base, rtol=1e-12)
+
+
+def test_eps_is_added_to_denominator(oracle):
+    rng = np.random.default_rng(7)
+    q, k, g, v = (_rand(rng, 1, 6, 1, 3) for _ in range(4))
+    r0 = oracle.gla_prefill(q, k, v, g)
+    r1 = oracle.gla_prefill(q, k, v, g, eps=0.5)
+    np.testing.assert_allclose(r1["den"], r0["den"] + 0.5, rtol=1e-14)
+    np.testing.assert_allclose(r1["o"], r0["num"] / (r0["den"] + 0.5)[..., None], rtol=1e-14)
+
+
+def test_causality_bit_exact(oracle):
+    rng = np.random.default_rng(8)
+    B, T, H, d = 1, 20, 2, 4
+    Q, K, V, G = (_rand(rng, B, T, H, d) for _ in range(4))
+    wq, wk = _rand(rng, H, d, 4), _rand(rng, H, d, 4)
+    r0 = oracle.layer_prefill(Q, K, V, G, wq, wk, feature_map=1)
+    cut = 11
+    Q2, K2, V2, G2 = (a.copy() for a in (Q, K, V, G))
+    for a in (Q2, K2, V2, G2):
+        a[:, cut:] = _rand(rng, B, T - cut, H, d)
+    r1 = oracle.layer_prefill(Q2, K2, V2, G2, wq, wk, feature_map=1)
+    assert np.array_equal(r0["o"][:, :cut], r1["o"][:, :cut])
+    assert not np.array_equal(r0["o"][:, cut:], r1["o"][:, cut:])
+
+
+# ---------------------------------------------------------------- conv (section 4.1)
+def test_conv_impulse_identity_and_shift(oracle):
+    rng = np.random.default_rng(9)
+    B, T, H, d, W = 2, 10, 3, 5, 4
+    x = _rand(rng, B, T, H, d)
+    for j in range(W):
+        w = np.zeros((H, d, W))
+        w[..., j] = 1.0
+        y = oracle.conv1d_causal(x, w)
+        ref = np.zeros_like(x)
+        ref[:, j:] = x[:, : T - j]
+        assert np.array_equal(y, ref)
+
+
+def test_conv_equals_toeplitz_and_library_correlation(oracle):
+    rng = np.random.default_rng(10)
+    B, T, H, d, W = 1, 17, 2, 3, 4
+    x, w = _rand(rng, B, T, H, d), _rand(rng, H, d, W)
+    y = oracle.conv1d_causal(x, w)
+    for h in range(H):
+        for c in range(d):
+            toe = np.zeros((T, T))
+            for t in range(T):
+                for dl in range(W):
+                    if t - dl >= 0:
+                        toe[t, t - dl] = w[h, c, dl]
+            np.testing.assert_allclose(y[0, :, h, c], toe @ x[0, :, h, c], rtol=1e-13, atol=1e-14)
+            # numpy's full convolution truncated to T samples is the same causal filter
+            np.testing.assert_allclose(y[0, :, h, c], np.convolve(x[0, :, h, c], w[h, c])[:T], rtol=1e-13, atol=1e-14)
+
+
+def test_conv_halo_equals_longer_sequence(oracle):
+    rng = np.random.default_rng(11)
+    B, T, H, d, W = 2, 9, 2, 3, 4
+    x, w = _rand(rng, B, T + W - 1, H, d), _rand(rng, H, d, W)
+    full = oracle.conv1d_causal(x, w, feature_map=1)
+    part = oracle.conv1d_causal(x[:, W - 1:], w, halo=x[:, : W - 1], feature_map=1)
+    np.testing.assert_allclose(part, full[:, W - 1:], rtol=1e-14)
+
+
+def test_feature_map_one_plus_elu(oracle):
+    x = np.array([-3.0, -0.5, 0.0, 0.5, 2.0]).reshape(1, 5, 1, 1)
+    w = np.zeros((1, 1, 4))
+    w[..., 0] = 1.0
+    y = oracle.conv1d_causal(x, w, feature_map=1).ravel()
+    np.testing.assert_allclose(y, [np.exp(-3.0), np.exp(-0.5), 1.0, 1.5, 3.0], rtol=1e-15)
+
+
+# ---------------------------------------------------------------- composition
+def test_continuation_split_prefill_and_steps(oracle):
+    """prefill(T) == prefill(T1) then prefill(T-T1) with carried (S, z, conv tails) == T single steps."""
+    rng = np.random.default_rng(12)
+    B, T, Hq, Hkv, d, W = 1, 21, 4, 2, 5, 4
+    Q = _rand(rng, B, T, Hq, d)
+    K, V, G = (_rand(rng, B, T, Hkv, d) for _ in range(3))
+    wq, wk = _rand(rng, Hq, d, W), _rand(rng, Hkv, d, W)
+    whole = oracle.layer_prefill(Q, K, V, G, wq, wk, feature_map=1)
+    T1 = 8
+    a = oracle.layer_prefill(Q[:, :T1], K[:, :T1], V[:, :T1], G[:, :T1], wq, wk, feature_map=1)
+    b = oracle.layer_prefill(Q[:, T1:], K[:, T1:], V[:, T1:], G[:, T1:], wq, wk, feature_map=1,
+                             S0=a["S"], z0=a["z"], q_halo=a["q_tail"], k_halo=a["k_tail"])
+    np.testing.assert_allclose(np.concatenate([a["o"], b["o"]], 1), whole["o"], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(b["S"], whole["S"], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(b["z"], whole["z"], rtol=1e-12, atol=1e-13)
+    assert np.array_equal(b["q_tail"], Q[:, -3:]) and np.array_equal(b["k_tail"], K[:, -3:])
+    # token-by-token decode: conv on one token with the cache, then one recurrent step
+    S = np.zeros((B, Hkv, d, d))
+    z = np.zeros((B, Hkv, d))
+    qc = np.zeros((B, W - 1, Hq, d))
+    kc = np.zeros((B, W - 1, Hkv, d))
+    for t in range(T):
+        qd = oracle.conv1d_causal(Q[:, t:t + 1], wq, qc, 1)[:, 0]
+        kd = oracle.conv1d_causal(K[:, t:t + 1], wk, kc, 1)[:, 0]
+        st = oracle.gla_step(qd, kd, V[:, t], G[:, t], S, z)
+        S, z = st["S"], st["z"]
+        qc = np.concatenate([qc[:, 1:], Q[:, t:t + 1]], 1)
+        kc = np.concatenate([kc[:, 1:], K[:, t:t + 1]], 1)
+        np.testing.assert_allclose(st["o"], whole["o"][:, t], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(S, whole["S"], rtol=1e-12, atol=1e-13)
+
+
+def chunked_fp64(q, k, v, g, C):
+    """Independent chunkwise evaluation (split the sum over i at chunk boundaries): for a
+    single head.  Used only to pin the recurrence against chunk-size invariance."""
+    T, dk = q.shape
+    dv = v.shape[1]
+    a = _logsig(g)
+    S = np.zeros((dk, dv))
+    z = np.zeros(dk)
+    o = np.zeros((T, dv))
+    for s0 in range(0, T, C):
+        s1 = min(T, s0 + C)
+        b = np.cumsum(a[s0:s1], axis=0)
+        qc, kc, vc = q[s0:s1], k[s0:s1], v[s0:s1]
+        n = s1 - s0
+        P = np.zeros((n, n))
+        for t in range(n):
+            for i in range(t + 1):
+                P[t, i] = np.sum(qc[t] * kc[i] * np.exp(b[t] - b[i]))
+        qe = qc * np.exp(b)
+        num = P @ vc + qe @ S
+        den = P.sum(1) + qe @ z
+        o[s0:s1] = num / den[:, None]
+        kd = kc * np.exp(b[-1] - b)
+        S = np.exp(b[-1])[:, None] * S + kd.T @ vc
+        z = np.exp(b[-1]) * z + kd.sum(0)
+    return o, S, z
+
+
+@pytest.mark.parametrize("C", [1, 2, 3, 16, 64, 100])
+def test_chunk_size_invariance(oracle, C):
+    rng = np.random.default_rng(13)
+    T, dk, dv = 100, 6, 5
+    q, k = np.exp(0.3 * _rand(rng, T, dk)), np.exp(0.3 * _rand(rng, T, dk))
+    g, v = _rand(rng, T, dk), _rand(rng, T, dv)
+    r = oracle.gla_prefill(q[None, :, None], k[None, :, None], v[None, :, None], g[None, :, None])
+    o, S, z = chunked_fp64(q, k, v, g, C)
+    np.testing.assert_allclose(r["o"][0, :, 0], o, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(r["S"][0, 0], S, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(r["z"][0, 0], z, rtol=1e-10, atol=1e-12)
+
+
+def test_input_generator_is_seeded_and_bf16_exact():
+    from paper_2509_18467_amd.inputs import WORKLOADS, Workload, make_inputs, round_to_bf16
+
+    wl = Workload("t", 1, 32, 4, 2, 64)
+    a, b = make_inputs(wl, 3), make_inputs(wl, 3)
+    for key in a:
+        assert np.array_equal(a[key], b[key])
+        assert np.array_equal(round_to_bf16(a[key]), a[key])  # already representable
+    import torch
+
+    x = np.random.default_rng(0).standard_normal(4096).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(round_to_bf16(x), ref)
+    assert make_inputs(WORKLOADS["tiny"])["Q"].shape == (1, 256, 2, 64)
+    w = make_inputs(WORKLOADS["tiny"])["wq"]
+    assert abs(w.var() - 0.25) < 0.03
