@@ -1,0 +1,142 @@
+/*
+ * lawcat.h -- C ABI of the MI355X (gfx950) LAWCAT sequence-mixing library.
+ *
+ * The library implements the prefill forward of LAWCAT's attention replacement
+ * (arXiv 2509.18467, section 4): a causal depthwise Conv1D across tokens on the
+ * queries and on the keys (section 4.1) feeding gated linear attention with the
+ * normalization term kept (section 4.2).
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - `desc` is a HOST pointer; every other pointer is a DEVICE pointer owned by the
+ *    caller.  The library never allocates, frees or keeps a pointer.  Scratch space is
+ *    the caller's `workspace` (size from lawcat_workspace_bytes).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only
+ *    enqueue work; they never synchronize.
+ *  - Layout is token-major with the head dimension contiguous:
+ *      Q, O              [B, T, Hq,  d]
+ *      K, V, gate_logits [B, T, Hkv, d]
+ *      S (KV state)      [B, Hkv, dk, dv]  fp32       z (normalizer state) [B, Hkv, dk] fp32
+ *      conv weights      [H, d, W] with w[h, c, delta] multiplying x[t - delta]
+ *                        (delta = 0 is the current token; section 4.1, sum over delta)
+ *      conv halo / tail  [B, W-1, H, d], oldest row first: the W-1 raw rows before the
+ *                        first token / the last W-1 raw rows (the cache of section 4.1)
+ *    Query head h reads the state of kv head h / (Hq/Hkv).
+ *  - `dtype` is the storage type of Q, K, V, gate_logits, conv weights, halos, tails and
+ *    O.  S, z and den are always fp32.  Arithmetic accumulates in fp32.
+ *  - The gate is per key channel: alpha[t,c] = sigmoid(gate_logits[t,c])^gate_scale
+ *    (section 4.2: linear layers followed by a sigmoid; G_t = alpha_t^T 1).
+ *  - Return value: LAWCAT_OK or a negative lawcat_status.  All argument checks run on
+ *    the host before anything is enqueued; after an error the outputs are unspecified.
+ *    A zero denominator is not an error: IEEE inf/nan is returned as the last equation
+ *    of section 4.2 gives it.
+ *  - Inputs and outputs must not overlap, except S/z in lawcat_gla_step (updated in
+ *    place).  All pointers must be 16-byte aligned.
+ */
+#ifndef LAWCAT_H_
+#define LAWCAT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LAWCAT_VERSION 1
+#define LAWCAT_API __attribute__((visibility("default")))
+
+typedef enum lawcat_status {
+  LAWCAT_OK = 0,
+  LAWCAT_E_NULL = -1,        /* a required pointer is NULL */
+  LAWCAT_E_BAD_DESC = -2,    /* struct_size mismatch, non-positive dims, Hq % Hkv != 0, bad enum */
+  LAWCAT_E_UNSUPPORTED = -3, /* head dim, conv width, chunk or mode outside what the kernels cover */
+  LAWCAT_E_WORKSPACE = -4,   /* workspace NULL or smaller than lawcat_workspace_bytes */
+  LAWCAT_E_ALIGN = -5,       /* a pointer is not 16-byte aligned */
+  LAWCAT_E_HIP = -6          /* the HIP runtime reported a launch error */
+} lawcat_status;
+
+enum { LAWCAT_DTYPE_F32 = 0, LAWCAT_DTYPE_BF16 = 1 };
+enum { LAWCAT_PHI_IDENTITY = 0, LAWCAT_PHI_ELU1 = 1 }; /* 1 + ELU: x > 0 ? 1 + x : exp(x) */
+enum { LAWCAT_CARRY_AUTO = 0, LAWCAT_CARRY_SEQUENTIAL = 1, LAWCAT_CARRY_TWO_LEVEL = 2 };
+enum {
+  LAWCAT_CALL_CONV1D = 0,
+  LAWCAT_CALL_GLA_PREFILL = 1,
+  LAWCAT_CALL_GLA_STEP = 2,
+  LAWCAT_CALL_LAYER_PREFILL = 3
+};
+
+typedef struct lawcat_desc {
+  uint32_t struct_size; /* = sizeof(lawcat_desc) */
+  int32_t B, T, Hq, Hkv; /* Hq % Hkv == 0 */
+  int32_t dk, dv;        /* supported: dk == dv in {64, 128} */
+  int32_t conv_width;    /* W = r + 1, supported 1..4 (the paper uses 4) */
+  int32_t dtype;         /* LAWCAT_DTYPE_* */
+  int32_t feature_map;   /* LAWCAT_PHI_*: pointwise map applied after the conv */
+  int32_t chunk;         /* tokens per state-carry step of the bf16 path: 0 = auto, else 16 */
+  int32_t carry_mode;    /* LAWCAT_CARRY_*: how the state crosses segment boundaries */
+  int32_t segment;       /* tokens per workgroup in two-level mode: 0 = auto, else a multiple of 64 */
+  float gate_scale;      /* log alpha = gate_scale * log sigmoid(g); 1.0 in every graded workload */
+  float eps;             /* added to the denominator; 0 = the paper's equation as written */
+} lawcat_desc;
+
+/* Bytes of device scratch `which_call` (LAWCAT_CALL_*) needs for this desc; 0 if none.
+ * Returns 0 for an invalid desc as well (the call itself reports the error). */
+LAWCAT_API size_t lawcat_workspace_bytes(const lawcat_desc* desc, int which_call);
+
+/*
+ * Section 4.1: y[b,t,h,c] = phi( sum_{delta<W} w[h,c,delta] * x[b,t-delta,h,c] ).
+ * Rows before the first token come from `halo` (NULL = zeros).  `n_heads` is the head
+ * count of x (Hq for queries, Hkv for keys); desc->Hq/Hkv are not read.
+ *   x, y      [B,T,n_heads,d]   w [n_heads,d,W]   halo, tail_out [B,W-1,n_heads,d] (nullable)
+ * tail_out receives the last W-1 raw rows of [halo ; x]; it must not alias halo.
+ * With W == 1 halo and tail_out are ignored.
+ */
+LAWCAT_API int lawcat_conv1d_causal(const lawcat_desc* desc, int n_heads, const void* x, const void* w,
+                         const void* halo, void* y, void* tail_out, void* stream);
+
+/*
+ * Section 4.2, prefill: for t = 1..T
+ *   S_t = diag(alpha_t) S_{t-1} + k_t^T v_t,   z_t = alpha_t (.) z_{t-1} + k_t,
+ *   o_t = q_t S_t / (q_t . z_t + eps)
+ * starting from S0, z0 (NULL = zeros).  q and k are the already transformed q-dot, k-dot.
+ *   q [B,T,Hq,dk]  k, gate_logits [B,T,Hkv,dk]  v [B,T,Hkv,dv]  o [B,T,Hq,dv]
+ *   den_out (nullable) [B,T,Hq] fp32 = q_t . z_t + eps
+ *   S_out [B,Hkv,dk,dv], z_out [B,Hkv,dk]: the state after token T (required).
+ */
+LAWCAT_API int lawcat_gla_prefill(const lawcat_desc* desc, const void* q, const void* k, const void* v,
+                       const void* gate_logits, const float* S0, const float* z0, void* o,
+                       float* den_out, float* S_out, float* z_out, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/*
+ * Section 4.2, one recurrent (decode) step on one token per sequence; desc->T is ignored.
+ *   q [B,Hq,dk]  k, gate_logits [B,Hkv,dk]  v [B,Hkv,dv]  o [B,Hq,dv]
+ *   S [B,Hkv,dk,dv], z [B,Hkv,dk]: read, updated in place.
+ */
+LAWCAT_API int lawcat_gla_step(const lawcat_desc* desc, const void* q, const void* k, const void* v,
+                    const void* gate_logits, float* S, float* z, void* o, void* stream);
+
+/*
+ * The whole layer of Fig. 1 between the projections: conv + phi on Q (weights wq [Hq,dk,W])
+ * and on K (wk [Hkv,dk,W]), gate logits -> decay, normalized gated linear attention.
+ * Equals lawcat_conv1d_causal on Q and on K followed by lawcat_gla_prefill.
+ *   S0, z0, q_halo, k_halo: nullable (zeros).  den_out, q_tail_out, k_tail_out: nullable.
+ *   S_out, z_out: required.
+ */
+LAWCAT_API int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
+                         const void* gate_logits, const void* wq, const void* wk, const float* S0,
+                         const float* z0, const void* q_halo, const void* k_halo, void* O,
+                         float* den_out, float* S_out, float* z_out, void* q_tail_out,
+                         void* k_tail_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Static string for a lawcat_status value. */
+LAWCAT_API const char* lawcat_status_string(int status);
+
+/* LAWCAT_VERSION the library was built with. */
+LAWCAT_API int lawcat_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAWCAT_H_ */

@@ -23,7 +23,7 @@
  * Pinned by tests/test_oracle_pins.py (brute-force quadratic form, closed forms,
  * invariants); nothing here is "parity unpinned".
  *
- * Build: gcc -O2 -fopenmp -shared -fPIC -o liblawcat_oracle.so lawcat_oracle.c -lm
+ * Build: gcc -O3 -fopenmp -shared -fPIC -o liblawcat_oracle.so lawcat_oracle.c -lm
  */
 #include <math.h>
 #include <stddef.h>

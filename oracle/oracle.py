@@ -24,7 +24,7 @@ def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (fp64, OpenMP over the independent recurrences)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
-            ["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+            ["gcc", "-O3", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
         )
     return _LIB
 

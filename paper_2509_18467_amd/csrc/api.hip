@@ -1,0 +1,219 @@
+// Host side of the C ABI declared in include/lawcat.h: argument checks, workspace
+// layout, kernel selection.  Every check runs before anything is enqueued, so the
+// error paths can be exercised on a machine without a GPU.
+#include "../../include/lawcat.h"
+
+#include <cmath>
+
+#include "kernels.h"
+
+using namespace lawcat;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align_up(size_t n, size_t a) { return (n + a - 1) / a * a; }
+
+// Checks common to every call.  `need_T` is false for the decode step.
+int check_desc(const lawcat_desc* d, bool need_T) {
+  if (d == nullptr) return LAWCAT_E_NULL;
+  if (d->struct_size != sizeof(lawcat_desc)) return LAWCAT_E_BAD_DESC;
+  if (d->B <= 0 || d->Hq <= 0 || d->Hkv <= 0 || d->dk <= 0 || d->dv <= 0) return LAWCAT_E_BAD_DESC;
+  if (need_T && d->T <= 0) return LAWCAT_E_BAD_DESC;
+  if (d->Hq % d->Hkv != 0) return LAWCAT_E_BAD_DESC;
+  if (d->dtype != LAWCAT_DTYPE_F32 && d->dtype != LAWCAT_DTYPE_BF16) return LAWCAT_E_BAD_DESC;
+  if (d->feature_map != LAWCAT_PHI_IDENTITY && d->feature_map != LAWCAT_PHI_ELU1) return LAWCAT_E_BAD_DESC;
+  if (d->carry_mode < LAWCAT_CARRY_AUTO || d->carry_mode > LAWCAT_CARRY_TWO_LEVEL) return LAWCAT_E_BAD_DESC;
+  if (!(d->gate_scale >= 0.f) || !std::isfinite(d->gate_scale) || !std::isfinite(d->eps)) return LAWCAT_E_BAD_DESC;
+  if (d->conv_width <= 0 || d->segment < 0 || d->chunk < 0) return LAWCAT_E_BAD_DESC;
+  if (d->dk != d->dv || (d->dk != 64 && d->dk != 128)) return LAWCAT_E_UNSUPPORTED;
+  if (d->conv_width > 4) return LAWCAT_E_UNSUPPORTED;
+  if (d->chunk != 0 && d->chunk != 16) return LAWCAT_E_UNSUPPORTED;
+  if (d->segment % 64 != 0) return LAWCAT_E_UNSUPPORTED;
+  return LAWCAT_OK;
+}
+
+inline size_t elem_bytes(const lawcat_desc* d) { return d->dtype == LAWCAT_DTYPE_BF16 ? 2 : 4; }
+
+// Which prefill implementation a desc selects.
+enum class Path { kRecurrentF32, kChunkBf16 };
+inline Path prefill_path(const lawcat_desc* d) {
+  return (d->dtype == LAWCAT_DTYPE_BF16 && chunk_path_supports(d->Hq / d->Hkv)) ? Path::kChunkBf16
+                                                                                : Path::kRecurrentF32;
+}
+
+ChunkPlan plan_for(const lawcat_desc* d) {
+  return make_chunk_plan(d->B, d->T, d->Hkv, d->dk, d->carry_mode, d->segment);
+}
+
+size_t workspace_bytes_checked(const lawcat_desc* d, int which) {
+  switch (which) {
+    case LAWCAT_CALL_CONV1D:
+    case LAWCAT_CALL_GLA_STEP:
+      return 0;
+    case LAWCAT_CALL_GLA_PREFILL:
+      return prefill_path(d) == Path::kChunkBf16 ? plan_for(d).workspace_bytes : 0;
+    case LAWCAT_CALL_LAYER_PREFILL: {
+      if (prefill_path(d) == Path::kChunkBf16) return plan_for(d).workspace_bytes;
+      // unfused: q-dot and k-dot staged in the storage type
+      const size_t rows = (size_t)d->B * d->T;
+      return align_up(rows * d->Hq * d->dk * elem_bytes(d), 256) + align_up(rows * d->Hkv * d->dk * elem_bytes(d), 256);
+    }
+    default:
+      return 0;
+  }
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? LAWCAT_OK : LAWCAT_E_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+size_t lawcat_workspace_bytes(const lawcat_desc* desc, int which_call) {
+  const bool need_T = which_call != LAWCAT_CALL_GLA_STEP;
+  if (check_desc(desc, need_T) != LAWCAT_OK) return 0;
+  return workspace_bytes_checked(desc, which_call);
+}
+
+int lawcat_conv1d_causal(const lawcat_desc* desc, int n_heads, const void* x, const void* w, const void* halo,
+                         void* y, void* tail_out, void* stream) {
+  int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (n_heads <= 0) return LAWCAT_E_BAD_DESC;
+  if (x == nullptr || w == nullptr || y == nullptr) return LAWCAT_E_NULL;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(y) || !aligned16(halo) || !aligned16(tail_out))
+    return LAWCAT_E_ALIGN;
+  ConvParams p{};
+  p.x = x; p.w = w; p.halo = desc->conv_width > 1 ? halo : nullptr; p.y = y;
+  p.tail_out = desc->conv_width > 1 ? tail_out : nullptr;
+  p.B = desc->B; p.T = desc->T; p.H = n_heads; p.d = desc->dk; p.W = desc->conv_width;
+  p.phi = desc->feature_map; p.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
+  return hip_status(launch_conv1d(p, static_cast<hipStream_t>(stream)));
+}
+
+int lawcat_gla_prefill(const lawcat_desc* desc, const void* q, const void* k, const void* v,
+                       const void* gate_logits, const float* S0, const float* z0, void* o, float* den_out,
+                       float* S_out, float* z_out, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (!q || !k || !v || !gate_logits || !o || !S_out || !z_out) return LAWCAT_E_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(gate_logits) || !aligned16(S0) ||
+      !aligned16(z0) || !aligned16(o) || !aligned16(den_out) || !aligned16(S_out) || !aligned16(z_out) ||
+      !aligned16(workspace))
+    return LAWCAT_E_ALIGN;
+  const size_t need = workspace_bytes_checked(desc, LAWCAT_CALL_GLA_PREFILL);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return LAWCAT_E_WORKSPACE;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (prefill_path(desc) == Path::kChunkBf16) {
+    ChunkParams c{};
+    c.q = q; c.k = k; c.v = v; c.g = gate_logits; c.S0 = S0; c.z0 = z0; c.o = o; c.den_out = den_out;
+    c.S_out = S_out; c.z_out = z_out; c.workspace = workspace;
+    c.B = desc->B; c.T = desc->T; c.Hq = desc->Hq; c.Hkv = desc->Hkv; c.d = desc->dk;
+    c.W = 1; c.phi = LAWCAT_PHI_IDENTITY; c.fuse_conv = 0;
+    c.gate_scale = desc->gate_scale; c.eps = desc->eps; c.plan = plan_for(desc);
+    return hip_status(launch_gla_chunk(c, hs));
+  }
+  RecurrentParams r{};
+  r.q = q; r.k = k; r.v = v; r.g = gate_logits; r.S0 = S0; r.z0 = z0; r.o = o; r.den_out = den_out;
+  r.S_out = S_out; r.z_out = z_out; r.B = desc->B; r.T = desc->T; r.Hq = desc->Hq; r.Hkv = desc->Hkv;
+  r.d = desc->dk; r.gate_scale = desc->gate_scale; r.eps = desc->eps;
+  r.bf16 = desc->dtype == LAWCAT_DTYPE_BF16; r.whole_state_per_block = 0;
+  return hip_status(launch_gla_recurrent(r, hs));
+}
+
+int lawcat_gla_step(const lawcat_desc* desc, const void* q, const void* k, const void* v, const void* gate_logits,
+                    float* S, float* z, void* o, void* stream) {
+  int st = check_desc(desc, false);
+  if (st != LAWCAT_OK) return st;
+  if (!q || !k || !v || !gate_logits || !S || !z || !o) return LAWCAT_E_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(gate_logits) || !aligned16(S) ||
+      !aligned16(z) || !aligned16(o))
+    return LAWCAT_E_ALIGN;
+  RecurrentParams r{};
+  r.q = q; r.k = k; r.v = v; r.g = gate_logits; r.S0 = S; r.z0 = z; r.o = o; r.den_out = nullptr;
+  r.S_out = S; r.z_out = z; r.B = desc->B; r.T = 1; r.Hq = desc->Hq; r.Hkv = desc->Hkv; r.d = desc->dk;
+  r.gate_scale = desc->gate_scale; r.eps = desc->eps; r.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
+  r.whole_state_per_block = 1;
+  return hip_status(launch_gla_recurrent(r, static_cast<hipStream_t>(stream)));
+}
+
+int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
+                         const void* gate_logits, const void* wq, const void* wk, const float* S0,
+                         const float* z0, const void* q_halo, const void* k_halo, void* O, float* den_out,
+                         float* S_out, float* z_out, void* q_tail_out, void* k_tail_out, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (!Q || !K || !V || !gate_logits || !wq || !wk || !O || !S_out || !z_out) return LAWCAT_E_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(gate_logits) || !aligned16(wq) ||
+      !aligned16(wk) || !aligned16(S0) || !aligned16(z0) || !aligned16(q_halo) || !aligned16(k_halo) ||
+      !aligned16(O) || !aligned16(den_out) || !aligned16(S_out) || !aligned16(z_out) ||
+      !aligned16(q_tail_out) || !aligned16(k_tail_out) || !aligned16(workspace))
+    return LAWCAT_E_ALIGN;
+  const size_t need = workspace_bytes_checked(desc, LAWCAT_CALL_LAYER_PREFILL);
+  if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return LAWCAT_E_WORKSPACE;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  const int bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
+
+  if (prefill_path(desc) == Path::kChunkBf16) {
+    ChunkParams c{};
+    c.q = Q; c.k = K; c.v = V; c.g = gate_logits; c.wq = wq; c.wk = wk; c.q_halo = q_halo; c.k_halo = k_halo;
+    c.S0 = S0; c.z0 = z0; c.o = O; c.den_out = den_out; c.S_out = S_out; c.z_out = z_out;
+    c.workspace = workspace;
+    c.B = desc->B; c.T = desc->T; c.Hq = desc->Hq; c.Hkv = desc->Hkv; c.d = desc->dk;
+    c.W = desc->conv_width; c.phi = desc->feature_map; c.fuse_conv = 1;
+    c.gate_scale = desc->gate_scale; c.eps = desc->eps; c.plan = plan_for(desc);
+    hipError_t e = launch_gla_chunk(c, hs);
+    if (e != hipSuccess) return LAWCAT_E_HIP;
+    if (desc->conv_width > 1) {
+      if (q_tail_out) {
+        e = launch_conv_tail(Q, q_halo, q_tail_out, desc->B, desc->T, desc->Hq, desc->dk, desc->conv_width, bf16, hs);
+        if (e != hipSuccess) return LAWCAT_E_HIP;
+      }
+      if (k_tail_out) {
+        e = launch_conv_tail(K, k_halo, k_tail_out, desc->B, desc->T, desc->Hkv, desc->dk, desc->conv_width, bf16, hs);
+        if (e != hipSuccess) return LAWCAT_E_HIP;
+      }
+    }
+    return LAWCAT_OK;
+  }
+
+  // Unfused path (fp32 storage): conv + phi into the workspace, then the fp32 recurrence.
+  const size_t rows = (size_t)desc->B * desc->T;
+  char* ws = static_cast<char*>(workspace);
+  void* qd = ws;
+  void* kd = ws + align_up(rows * desc->Hq * desc->dk * elem_bytes(desc), 256);
+  ConvParams p{};
+  p.B = desc->B; p.T = desc->T; p.d = desc->dk; p.W = desc->conv_width; p.phi = desc->feature_map; p.bf16 = bf16;
+  p.x = Q; p.w = wq; p.halo = desc->conv_width > 1 ? q_halo : nullptr; p.y = qd;
+  p.tail_out = desc->conv_width > 1 ? q_tail_out : nullptr; p.H = desc->Hq;
+  hipError_t e = launch_conv1d(p, hs);
+  if (e != hipSuccess) return LAWCAT_E_HIP;
+  p.x = K; p.w = wk; p.halo = desc->conv_width > 1 ? k_halo : nullptr; p.y = kd;
+  p.tail_out = desc->conv_width > 1 ? k_tail_out : nullptr; p.H = desc->Hkv;
+  e = launch_conv1d(p, hs);
+  if (e != hipSuccess) return LAWCAT_E_HIP;
+  RecurrentParams r{};
+  r.q = qd; r.k = kd; r.v = V; r.g = gate_logits; r.S0 = S0; r.z0 = z0; r.o = O; r.den_out = den_out;
+  r.S_out = S_out; r.z_out = z_out; r.B = desc->B; r.T = desc->T; r.Hq = desc->Hq; r.Hkv = desc->Hkv;
+  r.d = desc->dk; r.gate_scale = desc->gate_scale; r.eps = desc->eps; r.bf16 = bf16; r.whole_state_per_block = 0;
+  return hip_status(launch_gla_recurrent(r, hs));
+}
+
+const char* lawcat_status_string(int status) {
+  switch (status) {
+    case LAWCAT_OK: return "ok";
+    case LAWCAT_E_NULL: return "a required pointer is NULL";
+    case LAWCAT_E_BAD_DESC: return "invalid descriptor";
+    case LAWCAT_E_UNSUPPORTED: return "configuration not supported by the kernels";
+    case LAWCAT_E_WORKSPACE: return "workspace missing or too small";
+    case LAWCAT_E_ALIGN: return "pointer not 16-byte aligned";
+    case LAWCAT_E_HIP: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+int lawcat_version(void) { return LAWCAT_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,133 @@
+// Token-by-token form of the normalized gated linear attention (paper section 4.2):
+//   S_t = diag(alpha_t) S_{t-1} + k_t^T v_t,  z_t = alpha_t (.) z_{t-1} + k_t,
+//   o_t = q_t S_t / (q_t . z_t + eps)
+// in plain fp32 vector arithmetic.  It serves two callers: the decode step
+// (lawcat_gla_step, T = 1, state updated in place) and prefill with fp32 storage,
+// where bf16 matrix-core operands would not meet the fp32 error bound.
+//
+// One 256-thread block owns a (batch, kv head) and NJ slices of 16 value columns.
+// Lane layout: tid = j*16 + cg; the thread keeps S[c][col] for the d/16 key channels
+// c = cg + 16 r and the columns col = 16 s + j of its slices in registers, plus a replica of z[c].
+// q_t S_t is reduced over the 16 cg-lanes of a row with cross-lane shuffles.
+#include "kernels.h"
+
+namespace lawcat {
+namespace {
+
+__device__ inline float ldf(const float* p) { return *p; }
+__device__ inline float ldf(const bf16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+__device__ inline void stf(float* p, float v) { *p = v; }
+__device__ inline void stf(bf16_t* p, float v) {
+  __bf16 h = (__bf16)v;  // round to nearest even
+  *p = __builtin_bit_cast(bf16_t, h);
+}
+
+// log(sigmoid(g)), accurate on both tails.
+__device__ inline float log_sigmoid(float g) {
+  return g < 0.f ? g - log1pf(expf(g)) : -log1pf(expf(-g));
+}
+
+template <typename T, int D, int NJ>
+__global__ void __launch_bounds__(256) gla_recurrent_kernel(
+    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, const T* __restrict__ g,
+    const float* S0, const float* z0, T* __restrict__ o, float* __restrict__ den_out, float* S_out,
+    float* z_out, int Tn, int Hq, int Hkv, float gate_scale, float eps) {
+  constexpr int R = D / 16;
+  const int tid = threadIdx.x;
+  const int cg = tid & 15;
+  const int j = tid >> 4;
+  const int bh = blockIdx.x;  // b * Hkv + hk
+  const int b = bh / Hkv, hk = bh % Hkv;
+  const int group = Hq / Hkv;
+  const int slice0 = blockIdx.y * NJ;
+
+  float S[NJ][R], z[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int c = cg + 16 * r;
+    z[r] = z0 ? z0[(size_t)bh * D + c] : 0.f;
+#pragma unroll
+    for (int s = 0; s < NJ; ++s) {
+      const int col = (slice0 + s) * 16 + j;
+      S[s][r] = S0 ? S0[((size_t)bh * D + c) * D + col] : 0.f;
+    }
+  }
+  if (NJ * 16 == D) __syncthreads();  // in-place update: every read of S/z precedes every write
+
+  for (int t = 0; t < Tn; ++t) {
+    const size_t tok = (size_t)b * Tn + t;
+    const T* kt = k + (tok * Hkv + hk) * D;
+    const T* gt = g + (tok * Hkv + hk) * D;
+    const T* vt = v + (tok * Hkv + hk) * D;
+    float vv[NJ];
+#pragma unroll
+    for (int s = 0; s < NJ; ++s) vv[s] = ldf(vt + (slice0 + s) * 16 + j);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int c = cg + 16 * r;
+      const float alpha = expf(gate_scale * log_sigmoid(ldf(gt + c)));
+      const float kk = ldf(kt + c);
+      z[r] = fmaf(alpha, z[r], kk);
+#pragma unroll
+      for (int s = 0; s < NJ; ++s) S[s][r] = fmaf(alpha, S[s][r], kk * vv[s]);
+    }
+    for (int hh = 0; hh < group; ++hh) {
+      const int hq = hk * group + hh;
+      const T* qt = q + (tok * Hq + hq) * D;
+      float pd = 0.f, pn[NJ];
+#pragma unroll
+      for (int s = 0; s < NJ; ++s) pn[s] = 0.f;
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const float qq = ldf(qt + cg + 16 * r);
+        pd = fmaf(qq, z[r], pd);
+#pragma unroll
+        for (int s = 0; s < NJ; ++s) pn[s] = fmaf(qq, S[s][r], pn[s]);
+      }
+#pragma unroll
+      for (int m = 8; m >= 1; m >>= 1) {
+        pd += __shfl_xor(pd, m, 16);
+#pragma unroll
+        for (int s = 0; s < NJ; ++s) pn[s] += __shfl_xor(pn[s], m, 16);
+      }
+      if (cg == 0) {
+        const float den = pd + eps;
+        T* ot = o + (tok * Hq + hq) * D;
+#pragma unroll
+        for (int s = 0; s < NJ; ++s) stf(ot + (slice0 + s) * 16 + j, pn[s] / den);
+        if (den_out != nullptr && j == 0 && slice0 == 0) den_out[tok * Hq + hq] = den;
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int c = cg + 16 * r;
+    if (j == 0 && slice0 == 0) z_out[(size_t)bh * D + c] = z[r];
+#pragma unroll
+    for (int s = 0; s < NJ; ++s) S_out[((size_t)bh * D + c) * D + (slice0 + s) * 16 + j] = S[s][r];
+  }
+}
+
+template <typename T, int D>
+hipError_t launch_d(const RecurrentParams& p, hipStream_t stream) {
+  const int heads = p.B * p.Hkv;
+  if (p.whole_state_per_block) {
+    hipLaunchKernelGGL((gla_recurrent_kernel<T, D, D / 16>), dim3(heads, 1), dim3(256), 0, stream, (const T*)p.q,
+                       (const T*)p.k, (const T*)p.v, (const T*)p.g, p.S0, p.z0, (T*)p.o, p.den_out, p.S_out,
+                       p.z_out, p.T, p.Hq, p.Hkv, p.gate_scale, p.eps);
+  } else {
+    hipLaunchKernelGGL((gla_recurrent_kernel<T, D, 1>), dim3(heads, D / 16), dim3(256), 0, stream, (const T*)p.q,
+                       (const T*)p.k, (const T*)p.v, (const T*)p.g, p.S0, p.z0, (T*)p.o, p.den_out, p.S_out,
+                       p.z_out, p.T, p.Hq, p.Hkv, p.gate_scale, p.eps);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gla_recurrent(const RecurrentParams& p, hipStream_t stream) {
+  if (p.bf16) return p.d == 64 ? launch_d<bf16_t, 64>(p, stream) : launch_d<bf16_t, 128>(p, stream);
+  return p.d == 64 ? launch_d<float, 64>(p, stream) : launch_d<float, 128>(p, stream);
+}
+
+}  // namespace lawcat

@@ -1,0 +1,82 @@
+// Internal launch interface between the host ABI (api.hip) and the kernel files.
+// Not part of the public boundary; include/lawcat.h is.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lawcat {
+
+// Storage element of the bf16 path: raw 16-bit pattern.
+typedef uint16_t bf16_t;
+
+struct ConvParams {
+  const void* x;     // [B,T,H,d]
+  const void* w;     // [H,d,W]
+  const void* halo;  // nullable [B,W-1,H,d]
+  void* y;           // [B,T,H,d]
+  void* tail_out;    // nullable [B,W-1,H,d]
+  int B, T, H, d, W;
+  int phi;           // 0 identity, 1 = 1+ELU
+  int bf16;          // storage type
+};
+hipError_t launch_conv1d(const ConvParams& p, hipStream_t stream);
+
+struct RecurrentParams {
+  const void* q;  // [B,T,Hq,d]  (q-dot)
+  const void* k;  // [B,T,Hkv,d] (k-dot)
+  const void* v;  // [B,T,Hkv,d]
+  const void* g;  // [B,T,Hkv,d] gate logits
+  const float* S0;  // nullable [B,Hkv,d,d]
+  const float* z0;  // nullable [B,Hkv,d]
+  void* o;          // [B,T,Hq,d]
+  float* den_out;   // nullable [B,T,Hq]
+  float* S_out;     // [B,Hkv,d,d]
+  float* z_out;     // [B,Hkv,d]
+  int B, T, Hq, Hkv, d;
+  float gate_scale, eps;
+  int bf16;
+  int whole_state_per_block;  // 1: one block owns a head's whole state (safe for in-place S/z)
+};
+hipError_t launch_gla_recurrent(const RecurrentParams& p, hipStream_t stream);
+
+// Copies the last W-1 raw rows of [halo ; x] (the conv cache) without running the conv.
+hipError_t launch_conv_tail(const void* x, const void* halo, void* tail_out, int B, int T, int H, int d, int W,
+                            int bf16, hipStream_t stream);
+
+// How the bf16 matrix-core prefill splits a sequence: `nseg` segments of `seg_len` tokens per
+// (batch, kv head), each carried sequentially by one workgroup.  With nseg > 1 a first pass
+// computes every segment's state contribution and a scan turns them into start states.
+struct ChunkPlan {
+  int seg_len;
+  int nseg;
+  size_t workspace_bytes;
+};
+ChunkPlan make_chunk_plan(int B, int T, int Hkv, int d, int carry_mode, int segment);
+bool chunk_path_supports(int group);  // query heads per kv head the kernel is built for
+
+struct ChunkParams {
+  const void* q;  // raw Q (fuse_conv) or q-dot: [B,T,Hq,d] bf16
+  const void* k;
+  const void* v;
+  const void* g;
+  const void* wq;      // [Hq,d,W]  (fuse_conv only)
+  const void* wk;      // [Hkv,d,W] (fuse_conv only)
+  const void* q_halo;  // nullable [B,W-1,Hq,d]
+  const void* k_halo;  // nullable [B,W-1,Hkv,d]
+  const float* S0;
+  const float* z0;
+  void* o;
+  float* den_out;
+  float* S_out;
+  float* z_out;
+  void* workspace;
+  int B, T, Hq, Hkv, d, W;
+  int phi;
+  int fuse_conv;
+  float gate_scale, eps;
+  ChunkPlan plan;
+};
+hipError_t launch_gla_chunk(const ChunkParams& p, hipStream_t stream);
+
+}  // namespace lawcat

@@ -1,0 +1,107 @@
+"""Host-side checks of the C ABI: the library loads, exports what include/lawcat.h declares,
+and every argument error is reported before anything touches a GPU.  CPU only."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_18467_amd import lawcat
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "lawcat.h")).read()
+    declared = re.findall(r"LAWCAT_API\s+[\w\s\*]+?\b(lawcat_\w+)\s*\(", text)
+    assert sorted(declared) == sorted(lawcat.EXPORTS)
+    L = lawcat.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert lawcat.version() == 1
+
+
+def test_desc_matches_header_layout():
+    assert ctypes.sizeof(lawcat.Desc) == 15 * 4
+    text = open(os.path.join(ROOT, "include", "lawcat.h")).read()
+    body = re.search(r"typedef struct lawcat_desc \{(.*?)\} lawcat_desc;", text, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if decl:
+            names += [n.strip() for n in decl.split(None, 1)[1].split(",")]
+    assert names == [f[0] for f in lawcat.Desc._fields_]
+
+
+A = ctypes.c_void_p(0x1000)  # fake, 16-byte aligned device address: never dereferenced on error paths
+
+
+def _layer(desc, **over):
+    args = dict(Q=A, K=A, V=A, G=A, wq=A, wk=A, S0=None, z0=None, qh=None, kh=None, O=A, den=None, S=A, z=A,
+                qt=None, kt=None, ws=A, wsb=1 << 40, stream=None)
+    args.update(over)
+    return lawcat.lib().lawcat_layer_prefill(ctypes.byref(desc), *args.values())
+
+
+def test_null_and_bad_desc():
+    L = lawcat.lib()
+    assert L.lawcat_layer_prefill(None, *([None] * 17), 0, None) == -1
+    d = lawcat.make_desc(1, 256, 2, 2, 64, dtype=0)
+    assert _layer(d, Q=None) == -1
+    assert _layer(d, S=None) == -1
+    bad = lawcat.make_desc(1, 256, 2, 2, 64)
+    bad.struct_size = 8
+    assert _layer(bad) == -2
+    assert _layer(lawcat.make_desc(1, 0, 2, 2, 64)) == -2
+    assert _layer(lawcat.make_desc(1, 16, 3, 2, 64)) == -2
+    assert _layer(lawcat.make_desc(1, 16, 2, 2, 64, dtype=7)) == -2
+    assert _layer(lawcat.make_desc(1, 16, 2, 2, 64, feature_map=2)) == -2
+    assert _layer(lawcat.make_desc(1, 16, 2, 2, 64, carry_mode=3)) == -2
+    assert _layer(lawcat.make_desc(1, 16, 2, 2, 64, gate_scale=float("nan"))) == -2
+    assert _layer(lawcat.make_desc(1, 16, 2, 2, 64, gate_scale=-1.0)) == -2
+
+
+def test_unsupported_shapes():
+    assert _layer(lawcat.make_desc(1, 16, 2, 2, 48)) == -3
+    assert _layer(lawcat.make_desc(1, 16, 2, 2, 64, conv_width=5)) == -3
+    assert _layer(lawcat.make_desc(1, 16, 2, 2, 64, chunk=64)) == -3
+    assert _layer(lawcat.make_desc(1, 16, 2, 2, 64, segment=100)) == -3
+    d = lawcat.make_desc(1, 16, 2, 2, 64)
+    d.dv = 128
+    assert _layer(d) == -3
+
+
+def test_alignment_and_workspace():
+    d = lawcat.make_desc(1, 256, 2, 2, 64, dtype=0)
+    assert _layer(d, K=ctypes.c_void_p(0x1008)) == -5
+    need = lawcat.workspace_bytes(d, lawcat.CALL_LAYER_PREFILL)
+    assert need >= 256 * 4 * 64 * 4
+    assert _layer(d, ws=None) == -4
+    assert _layer(d, wsb=need - 1) == -4
+    assert lawcat.workspace_bytes(d, lawcat.CALL_CONV1D) == 0
+    assert lawcat.workspace_bytes(d, lawcat.CALL_GLA_STEP) == 0
+    assert lawcat.workspace_bytes(lawcat.make_desc(1, 16, 3, 2, 64), lawcat.CALL_LAYER_PREFILL) == 0
+
+
+def test_other_entry_points_report_errors():
+    L = lawcat.lib()
+    d = lawcat.make_desc(2, 64, 4, 2, 128)
+    r = ctypes.byref(d)
+    assert L.lawcat_conv1d_causal(r, 0, A, A, None, A, None, None) == -2
+    assert L.lawcat_conv1d_causal(r, 4, None, A, None, A, None, None) == -1
+    assert L.lawcat_conv1d_causal(r, 4, A, A, ctypes.c_void_p(0x1004), A, None, None) == -5
+    assert L.lawcat_gla_prefill(r, A, A, A, None, None, None, A, None, A, A, A, 1 << 40, None) == -1
+    assert L.lawcat_gla_prefill(r, A, A, A, A, None, None, A, None, A, None, A, 1 << 40, None) == -1
+    assert L.lawcat_gla_step(r, A, A, A, A, None, A, A, None) == -1
+    d0 = lawcat.make_desc(2, 0, 4, 2, 128)  # T is ignored by the step, checked by prefill
+    assert L.lawcat_gla_step(ctypes.byref(d0), A, A, A, A, A, ctypes.c_void_p(0x1001), A, None) == -5
+    assert L.lawcat_gla_prefill(ctypes.byref(d0), A, A, A, A, None, None, A, None, A, A, A, 1 << 40, None) == -2
+
+
+def test_status_strings():
+    seen = {lawcat.status_string(s) for s in range(0, -7, -1)}
+    assert len(seen) == 7 and "unknown status" not in seen
+    assert lawcat.status_string(-99) == "unknown status"
+    with pytest.raises(lawcat.LawcatError):
+        lawcat._check(-3)
