@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the LAWCAT prefill hot path on one MI355X.
+
+A step is one lawcat_layer_prefill call (conv + phi on Q and K, gate -> decay, normalized
+gated linear attention, final state and conv tails) over one seeded synthetic layer input
+that is already resident in HBM.  Prints ONE JSON line: prefill tokens/s per layer, the
+HBM roofline of the dominant kernel (the output pass) timed with HIP events, and the fp64 CPU
+oracle timed on the host cores as a baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sweep]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes_per_token(wl) -> int:
+    """Every tensor touched once, bf16: Q and O [Hq*d] each, K, V, gate logits [Hkv*d] each."""
+    esz = 2 if wl.dtype == "bf16" else 4
+    return esz * (2 * wl.Hq * wl.d + 3 * wl.Hkv * wl.d)
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs (ctypes on libamdhip64) for the library's output-pass trace hook."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.pairs = []
+        for _ in range(n):
+            a, b = ctypes.c_void_p(), ctypes.c_void_p()
+            assert self.hip.hipEventCreate(ctypes.byref(a)) == 0
+            assert self.hip.hipEventCreate(ctypes.byref(b)) == 0
+            self.pairs.append((a, b))
+
+    def elapsed_ms(self, i):
+        ms = ctypes.c_float()
+        a, b = self.pairs[i]
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        assert rc == 0, f"hipEventElapsedTime rc={rc}"
+        return ms.value
+
+    def destroy(self):
+        for a, b in self.pairs:
+            self.hip.hipEventDestroy(a)
+            self.hip.hipEventDestroy(b)
+
+
+def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0):
+    import torch
+
+    from paper_2509_18467_amd import lawcat
+    from paper_2509_18467_amd.inputs import make_inputs
+
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    desc = lawcat.make_desc(wl.B, wl.T, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W,
+                            dtype=lawcat.DTYPE_BF16 if wl.dtype == "bf16" else lawcat.DTYPE_F32,
+                            feature_map=feature_map)
+    bytes_step = algorithmic_bytes_per_token(wl) * wl.B * wl.T
+    # rotate input/output sets so the 256 MB Infinity Cache cannot serve a step's reads
+    nsets = max(2, min(12, -(-(1 << 30) // bytes_step)))
+    sets, host0 = [], None
+    for s in range(nsets):
+        x = make_inputs(wl, seed=seed + s)
+        if s == 0:
+            host0 = x
+        d = {k: torch.from_numpy(v).to("cuda").to(dt).contiguous() for k, v in x.items()}
+        d["O"] = torch.empty_like(d["Q"])
+        d["S"] = torch.empty(wl.B, wl.Hkv, wl.d, wl.d, dtype=torch.float32, device="cuda")
+        d["z"] = torch.empty(wl.B, wl.Hkv, wl.d, dtype=torch.float32, device="cuda")
+        d["qt"] = torch.empty(wl.B, wl.W - 1, wl.Hq, wl.d, dtype=dt, device="cuda")
+        d["kt"] = torch.empty(wl.B, wl.W - 1, wl.Hkv, wl.d, dtype=dt, device="cuda")
+        sets.append(d)
+    ws = lawcat.alloc_workspace(desc, lawcat.CALL_LAYER_PREFILL)
+
+    def step(i):
+        d = sets[i % nsets]
+        lawcat.layer_prefill(desc, d["Q"], d["K"], d["V"], d["G"], d["wq"], d["wk"], None, None, None, None,
+                             d["O"], None, d["S"], d["z"], d["qt"], d["kt"], ws)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = HipEvents(steps) if trace else None
+    t0 = time.perf_counter()
+    for i in range(steps):
+        if ev:
+            lawcat.trace_output_pass(ev.pairs[i][0].value, ev.pairs[i][1].value)
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    lawcat.trace_output_pass(None, None)
+    ms_step = (t1 - t0) * 1e3 / steps
+    kern_ms = None
+    if ev:
+        ks = sorted(ev.elapsed_ms(i) for i in range(steps))
+        kern_ms = sum(ks) / len(ks)
+        ev.destroy()
+    return {"ms_per_step": ms_step, "tokens_per_s": wl.B * wl.T / (ms_step * 1e-3), "kernel_ms": kern_ms,
+            "bytes_step": bytes_step, "nsets": nsets, "host0": host0}
+
+
+def cpu_baseline(wl, host0, feature_map=1, budget_tokens=None):
+    """The fp64 oracle as it stands, on the host cores, on a bounded prefix of the same inputs."""
+    from oracle import oracle
+
+    flop_tok = 2 * wl.d * wl.d * (wl.Hq + wl.Hkv)
+    # ~15 s at roughly 1.5 GFLOP/s per thread over min(cores, kv heads) threads
+    threads = min(oracle.max_threads(), wl.B * wl.Hkv)
+    Ts = budget_tokens or int(min(wl.T, max(1024, 15.0 * 1.5e9 * threads / flop_tok)))
+    x = {k: (v[:, :Ts] if k in "QKVG" else v) for k, v in host0.items()}
+    t0 = time.perf_counter()
+    oracle.layer_prefill(x["Q"], x["K"], x["V"], x["G"], x["wq"], x["wk"], feature_map)
+    dt = time.perf_counter() - t0
+    return {"value": wl.B * Ts / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"first {Ts} of {wl.T} tokens of the same seeded layer input, all heads, {dt:.1f} s"}
+
+
+def read_traffic(name):
+    """HBM bytes per output-pass launch from the committed rocprofv3 --pmc summary, if present."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{name}.json")
+    if os.path.exists(path):
+        with open(path) as f:
+            return json.load(f).get("traffic_bytes_per_launch")
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llama1b_32k")
+    ap.add_argument("--feature-map", type=int, default=1)
+    ap.add_argument("--sweep", action="store_true", help="also time the other graded shapes (reported under 'sweep')")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2509_18467_amd.inputs import WORKLOADS
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = WORKLOADS[args.workload]
+    r = run_workload(wl, args.steps, args.warmup, args.feature_map)
+    out = {
+        "metric": "prefill tokens/s per layer",
+        "value": r["tokens_per_s"],
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "T": wl.T, "Hq": wl.Hq, "Hkv": wl.Hkv, "head_dim": wl.d,
+                   "conv_width": wl.W, "feature_map": "1+elu" if args.feature_map == 1 else "identity",
+                   "input_sets_rotated": r["nsets"]},
+    }
+    if r["kernel_ms"]:
+        ach = r["bytes_step"] / (r["kernel_ms"] * 1e-3) / 1e9
+        out["roofline"] = {"bound": "hbm", "kernel": "gla_chunk_kernel (output pass)", "achieved": ach,
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                           "traffic": read_traffic(wl.name), "kernel_ms": r["kernel_ms"],
+                           "algorithmic_bytes_per_launch": r["bytes_step"],
+                           "whole_step_frac": r["bytes_step"] / (r["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    if args.sweep:
+        sweep = {}
+        for name in ("llama1b_8k", "llama1b_32k", "mistral7b_16k", "mistral7b_128k"):
+            if name == wl.name:
+                continue
+            w2 = WORKLOADS[name]
+            r2 = run_workload(w2, max(5, args.steps // 2), max(2, args.warmup // 2), args.feature_map)
+            sweep[name] = {"tokens_per_s": r2["tokens_per_s"], "ms_per_step": r2["ms_per_step"],
+                           "kernel_ms": r2["kernel_ms"],
+                           "whole_step_frac": r2["bytes_step"] / (r2["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            del r2
+            torch.cuda.empty_cache()
+        out["sweep"] = sweep
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(wl, r["host0"], args.feature_map)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -130,6 +130,14 @@ LAWCAT_API int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, cons
                          float* den_out, float* S_out, float* z_out, void* q_tail_out,
                          void* k_tail_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aid.  While both events (hipEvent_t passed as void*) are non-NULL, every prefill call
+ * that runs the bf16 matrix-core path records `before` just ahead of its output-pass kernel and
+ * `after` just behind it, on the call's stream, so a caller can time that kernel alone.  Pass NULLs
+ * to switch it off.  Process-wide state, not thread-safe; the events stay owned by the caller.
+ */
+LAWCAT_API void lawcat_trace_output_pass(void* before, void* after);
+
 /* Static string for a lawcat_status value. */
 LAWCAT_API const char* lawcat_status_string(int status);
 

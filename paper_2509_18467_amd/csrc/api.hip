@@ -201,6 +201,10 @@ int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, 
   return hip_status(launch_gla_recurrent(r, hs));
 }
 
+void lawcat_trace_output_pass(void* before, void* after) {
+  set_output_pass_events(static_cast<hipEvent_t>(before), static_cast<hipEvent_t>(after));
+}
+
 const char* lawcat_status_string(int status) {
   switch (status) {
     case LAWCAT_OK: return "ok";

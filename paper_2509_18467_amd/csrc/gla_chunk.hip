@@ -35,6 +35,8 @@ constexpr float kAlphaMin = 0.005524271728019903f;  // 2^-7.5
 constexpr float kInvAlphaMax = 181.01933598375618f;  // 2^7.5
 constexpr int kChunk = 16;
 
+hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
+
 struct ChunkArgs {
   const bf16_t *q, *k, *v, *g, *wq, *wk, *q_halo, *k_halo;
   const float *S0, *z0;
@@ -501,8 +503,16 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
   auto k3 = gla_chunk_kernel<D, GR, FUSE, true>;
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(k3), hipFuncAttributeMaxDynamicSharedMemorySize, G::kBytes);
   if (e != hipSuccess) return e;
+  const bool trace = g_ev_before != nullptr && g_ev_after != nullptr;
+  if (trace) {
+    e = hipEventRecord(g_ev_before, stream);
+    if (e != hipSuccess) return e;
+  }
   hipLaunchKernelGGL(k3, dim3(a.nseg, heads), dim3(256), G::kBytes, stream, a);
-  return hipGetLastError();
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (trace) e = hipEventRecord(g_ev_after, stream);
+  return e;
 }
 
 template <int D, int GR>
@@ -521,6 +531,11 @@ hipError_t launch_group(const ChunkArgs& a, int group, bool fuse, hipStream_t st
 }
 
 }  // namespace
+
+void set_output_pass_events(hipEvent_t before, hipEvent_t after) {
+  g_ev_before = before;
+  g_ev_after = after;
+}
 
 bool chunk_path_supports(int group) { return group == 1 || group == 2 || group == 4; }
 

@@ -78,5 +78,7 @@ struct ChunkParams {
   ChunkPlan plan;
 };
 hipError_t launch_gla_chunk(const ChunkParams& p, hipStream_t stream);
+// Events recorded around the output-pass kernel of launch_gla_chunk (nullptr = off).
+void set_output_pass_events(hipEvent_t before, hipEvent_t after);
 
 }  // namespace lawcat

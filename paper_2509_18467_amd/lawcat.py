@@ -21,7 +21,7 @@ CALL_CONV1D, CALL_GLA_PREFILL, CALL_GLA_STEP, CALL_LAYER_PREFILL = 0, 1, 2, 3
 
 EXPORTS = (
     "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gla_prefill", "lawcat_gla_step",
-    "lawcat_layer_prefill", "lawcat_status_string", "lawcat_version",
+    "lawcat_layer_prefill", "lawcat_trace_output_pass", "lawcat_status_string", "lawcat_version",
 )
 
 
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.lawcat_status_string.argtypes = [ci]
         L.lawcat_status_string.restype = ctypes.c_char_p
         L.lawcat_version.restype = ci
+        L.lawcat_trace_output_pass.argtypes = [vp, vp]
+        L.lawcat_trace_output_pass.restype = None
         _lib = L
     return _lib
 
@@ -80,6 +82,11 @@ def status_string(status: int) -> str:
 
 def version() -> int:
     return int(lib().lawcat_version())
+
+
+def trace_output_pass(before, after):
+    """before/after: raw hipEvent_t handles (ints) or None to switch tracing off."""
+    lib().lawcat_trace_output_pass(ctypes.c_void_p(before), ctypes.c_void_p(after))
 
 
 def make_desc(B, T, Hq, Hkv, d, *, conv_width=4, dtype=DTYPE_BF16, feature_map=PHI_ELU1, chunk=0,
