@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liblawcat.so")
-SOURCES = ["api.hip", "conv1d.hip", "gla_recurrent.hip", "gla_chunk.hip"]
+SOURCES = ["api.hip", "conv1d.hip", "gla_recurrent.hip", "gla_chunk.hip", "gla_chunk_d64.hip", "gla_chunk_d128.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off on purpose (toolchain notes)
 FLAGS = [
@@ -18,19 +18,25 @@ FLAGS = [
 ]
 
 
+# MFMA accumulators in architectural VGPRs (the state is rescaled by plain VALU multiplies every
+# 16 tokens, which AGPR-resident accumulators would have to be copied out for)
+PER_FILE_FLAGS = {"gla_chunk_d64.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def build(verbose: bool = False) -> str:
     objdir = os.path.join(_HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
 
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        extra = PER_FILE_FLAGS.get(src, [])
+        cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:

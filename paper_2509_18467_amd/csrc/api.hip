@@ -164,19 +164,8 @@ int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, 
     c.B = desc->B; c.T = desc->T; c.Hq = desc->Hq; c.Hkv = desc->Hkv; c.d = desc->dk;
     c.W = desc->conv_width; c.phi = desc->feature_map; c.fuse_conv = 1;
     c.gate_scale = desc->gate_scale; c.eps = desc->eps; c.plan = plan_for(desc);
-    hipError_t e = launch_gla_chunk(c, hs);
-    if (e != hipSuccess) return LAWCAT_E_HIP;
-    if (desc->conv_width > 1) {
-      if (q_tail_out) {
-        e = launch_conv_tail(Q, q_halo, q_tail_out, desc->B, desc->T, desc->Hq, desc->dk, desc->conv_width, bf16, hs);
-        if (e != hipSuccess) return LAWCAT_E_HIP;
-      }
-      if (k_tail_out) {
-        e = launch_conv_tail(K, k_halo, k_tail_out, desc->B, desc->T, desc->Hkv, desc->dk, desc->conv_width, bf16, hs);
-        if (e != hipSuccess) return LAWCAT_E_HIP;
-      }
-    }
-    return LAWCAT_OK;
+    c.q_tail = q_tail_out; c.k_tail = k_tail_out;
+    return hip_status(launch_gla_chunk(c, hs));
   }
 
   // Unfused path (fp32 storage): conv + phi into the workspace, then the fp32 recurrence.

@@ -1,0 +1,9 @@
+// Head dimension 64 instantiations of the matrix-core prefill kernels.
+#include "gla_chunk_impl.h"
+namespace lawcat {
+namespace chunk {
+hipError_t launch_d64(const ChunkArgs& a, int group, int mode, hipStream_t stream) {
+  return launch_d<64>(a, group, mode, stream);
+}
+}  // namespace chunk
+}  // namespace lawcat

@@ -1,0 +1,655 @@
+// bf16 matrix-core prefill of the normalized gated linear attention (paper section 4.2)
+// with the causal depthwise Conv1D of section 4.1 and the pointwise feature map fused into
+// the load stage.  Included by one translation unit per head dimension.
+//
+// Algebra.  Split the sum over i in the state/output equations of section 4.2 at the start
+// of a 16-token chunk.  With E_t = prod of alpha over the chunk's tokens up to t (per key
+// channel) the output of token t in the chunk is
+//   num_t = (q_t (.) E_t) S_start + sum_{i<=t} [(q_t (.) E_t) . (k_i / E_i)] v_i
+//   den_t = (q_t (.) E_t) z_start + sum_{i<=t} [(q_t (.) E_t) . (k_i / E_i)]
+// and the state after the chunk is S_end = diag(E_last) S_start + sum_i (k_i E_last/E_i)^T v_i.
+// All four products are bf16 MFMAs with fp32 accumulation.  The normalizer rides along as 16
+// extra value columns that are all ones, so num and den come out of the same MFMAs and the
+// division needs no cross-lane traffic.
+//
+// Parallel decomposition.  One 256-thread workgroup owns one (batch, kv head) and one
+// segment of the sequence, and walks it 16 tokens at a time with the [dk x (dv+16)] state in
+// MFMA accumulators; the query heads of the group share k, v, the decay and the state.  With
+// more than one segment a first pass computes each segment's state contribution and total
+// decay, a small scan turns them into segment start states, and the output pass starts from
+// those.
+//
+// Per-step decay is floored at 2^-7.5 so that a chunk's 1/E stays below 2^120.
+#pragma once
+#include "kernels.h"
+
+namespace lawcat {
+namespace chunk {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kAlphaMin = 0.005524271728019903f;   // 2^-7.5
+constexpr float kInvAlphaMax = 181.01933598375618f;  // 2^7.5
+constexpr int kChunk = 16;
+
+// MODE of the load stage
+constexpr int kPlain = 0;     // q, k are already q-dot, k-dot (lawcat_gla_prefill)
+constexpr int kConvId = 1;    // conv, identity feature map
+constexpr int kConvElu = 2;   // conv, 1 + ELU
+
+struct ChunkArgs {
+  const bf16_t *q, *k, *v, *g, *wq, *wk, *q_halo, *k_halo;
+  const float *S0, *z0;
+  bf16_t* o;
+  float* den_out;
+  float* S_out;
+  float* z_out;
+  bf16_t *q_tail, *k_tail;
+  float* ws;
+  int B, T, Hq, Hkv, W;
+  int seg_len, nseg;
+  float gate_scale, eps;
+};
+
+template <int D, int GR>
+struct Geo {
+  static constexpr int CH = D / 64;          // 64-channel slabs per row = waves per 16-token chunk in the load stage
+  static constexpr int NTG = 4096 / D;       // tokens per granule (one load stage of the workgroup)
+  static constexpr int MCG = NTG / kChunk;   // chunks per granule
+  static constexpr int RT = D / 16;          // 16-row tiles of the state (key channels)
+  static constexpr int CT = D / 64;          // value-column tiles owned by a wave
+  static constexpr int NT = CT + 1;          // plus the normalizer tile
+  static constexpr int KS = D / 32;          // k-steps of a 16x16x32 MFMA over the key channels
+  static constexpr int QRS = D * 2 + 8;      // LDS row stride (bytes) of token-major bf16 rows
+  static constexpr int TRS = NTG * 2 + 8;    // LDS row stride (bytes) of channel-major bf16 rows
+  static constexpr int kQp = 0;
+  static constexpr int kKp = kQp + GR * NTG * QRS;
+  static constexpr int kKd = kKp + NTG * QRS;
+  static constexpr int kVt = kKd + D * TRS;
+  static constexpr int kEb = kVt + D * TRS;
+  static constexpr int kWl = kEb + MCG * D * 4;
+  static constexpr int kBytes = kWl + (GR + 1) * D * 16;
+  static constexpr int kSlot = D * D + 2 * D;  // floats per workspace slot: S | z | decay
+};
+
+__device__ inline float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ inline float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ inline uint32_t pack2(float a, float b) {
+  bf16x2 v = {(__bf16)a, (__bf16)b};  // v_cvt_pk_bf16_f32, round to nearest even
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ inline float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ inline float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+
+// Raw input rows of one granule held in registers between the load and the compute stage:
+// one dword = two adjacent channels of one token.  Index j is row tok0 - 3 + j: three rows of conv
+// history (keys and queries only), then the patch's eight tokens.
+template <int NQ>
+struct Raw {
+  uint32_t g[11];
+  uint32_t k[11];
+  uint32_t v[11];
+  uint32_t q[NQ][11];
+};
+
+// Uniform (per workgroup) row addressing of one input tensor.
+struct RowSrc {
+  const char* base;   // first row of this batch, at this head's columns
+  const char* halo;   // nullable: first halo row of this batch, at this head's columns
+  unsigned stride;    // bytes per token row
+};
+
+// Interior granule: every row t0-3 .. t0+NTG-1 exists.  Scalar row base + one per-thread offset.
+template <bool CONV>
+__device__ inline void load_rows_interior(const RowSrc& s, int t0, unsigned voff, uint32_t (&raw)[11]) {
+  const char* gb = s.base + (size_t)(t0 - 3) * s.stride;
+#pragma unroll
+  for (int j = CONV ? 0 : 3; j < 11; ++j)
+    raw[j] = *reinterpret_cast<const uint32_t*>(gb + (size_t)j * s.stride + voff);
+}
+
+// Edge granule (start of the sequence or ragged end): rows before the sequence come from the halo
+// or are zero, rows at or past `tend` are zero.
+template <bool CONV>
+__device__ inline void load_rows_edge(const RowSrc& s, int tok0, int tend, int W, unsigned coff, uint32_t (&raw)[11]) {
+#pragma unroll
+  for (int j = CONV ? 0 : 3; j < 11; ++j) {
+    const int tok = tok0 - 3 + j;
+    uint32_t r = 0u;
+    if (tok >= 0) {
+      if (tok < tend) r = *reinterpret_cast<const uint32_t*>(s.base + (size_t)tok * s.stride + coff);
+    } else if (CONV && s.halo != nullptr && tok >= -(W - 1)) {
+      r = *reinterpret_cast<const uint32_t*>(s.halo + (size_t)(W - 1 + tok) * s.stride + coff);
+    }
+    raw[j] = r;
+  }
+}
+
+// conv (section 4.1 sum over delta) + feature map on the 8 tokens x 2 channels of a patch.
+// For MODE kConvElu the weights arrive pre-multiplied by log2(e): with y' = y log2(e),
+// 1 + ELU(y) = ln2 * max(y', 0) + min(2^y', 1).
+template <int MODE>
+__device__ inline void conv_phi(const uint32_t (&raw)[11], const float* wts /*[2][4] in LDS*/, float (&y)[8][2]) {
+  if (MODE == kPlain) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { y[i][0] = bf_lo(raw[i + 3]); y[i][1] = bf_hi(raw[i + 3]); }
+    return;
+  }
+  const floatx4 w0 = *reinterpret_cast<const floatx4*>(wts);
+  const floatx4 w1 = *reinterpret_cast<const floatx4*>(wts + 4);
+  float x0[11], x1[11];
+#pragma unroll
+  for (int j = 0; j < 11; ++j) { x0[j] = bf_lo(raw[j]); x1[j] = bf_hi(raw[j]); }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float a0 = w0[0] * x0[i + 3];
+    a0 = fmaf(w0[1], x0[i + 2], a0); a0 = fmaf(w0[2], x0[i + 1], a0); a0 = fmaf(w0[3], x0[i], a0);
+    float a1 = w1[0] * x1[i + 3];
+    a1 = fmaf(w1[1], x1[i + 2], a1); a1 = fmaf(w1[2], x1[i + 1], a1); a1 = fmaf(w1[3], x1[i], a1);
+    if (MODE == kConvElu) {
+      a0 = fmaf(fmaxf(a0, 0.f), kLn2, fminf(fast_exp2(a0), 1.f));
+      a1 = fmaf(fmaxf(a1, 0.f), kLn2, fminf(fast_exp2(a1), 1.f));
+    }
+    y[i][0] = a0;
+    y[i][1] = a1;
+  }
+}
+
+template <int D, int GR, int MODE, bool OUTPUT>
+struct Kernel {
+  using G = Geo<D, GR>;
+  static constexpr bool CONV = MODE != kPlain;
+  static constexpr int NQ = OUTPUT ? GR : 1;
+
+  // ---- HBM -> registers: the raw rows of the granule starting at token t0
+  __device__ static inline void fetch(Raw<NQ>& raw, const RowSrc& srcK, const RowSrc& srcG, const RowSrc& srcV,
+                                      const RowSrc& srcQ, int t0, int s1, int tl0, unsigned coff, int W) {
+    const bool edge = (t0 < 3) || (t0 + G::NTG > s1);
+    if (!edge) {
+      const unsigned voffkv = (unsigned)tl0 * srcK.stride + coff;
+      load_rows_interior<false>(srcG, t0, voffkv, raw.g);
+      load_rows_interior<CONV>(srcK, t0, voffkv, raw.k);
+      load_rows_interior<false>(srcV, t0, voffkv, raw.v);
+      if (OUTPUT) {
+        const unsigned voffq = (unsigned)tl0 * srcQ.stride + coff;
+#pragma unroll
+        for (int hh = 0; hh < NQ; ++hh) load_rows_interior<CONV>(srcQ, t0, voffq + hh * D * 2, raw.q[hh]);
+      }
+    } else {
+      const int tok0 = t0 + tl0;
+      load_rows_edge<false>(srcG, tok0, s1, 1, coff, raw.g);
+      load_rows_edge<CONV>(srcK, tok0, s1, W, coff, raw.k);
+      load_rows_edge<false>(srcV, tok0, s1, 1, coff, raw.v);
+      if (OUTPUT) {
+#pragma unroll
+        for (int hh = 0; hh < NQ; ++hh) load_rows_edge<CONV>(srcQ, tok0, s1, W, coff + hh * D * 2, raw.q[hh]);
+      }
+    }
+  }
+
+  // ---- registers -> LDS operands: gate products, conv + phi, scaling by the decay, bf16 packing
+  template <bool EDGE>
+  __device__ static inline void compute(const Raw<NQ>& raw, unsigned char* smem, const float* wl, int t0, int s1,
+                                        int tl0, int c0, int mcw, int th, bool gs1, float gate_scale) {
+    const int tok0 = t0 + tl0;
+    float E[8][2], IE[8][2];
+    float run[2] = {1.f, 1.f}, irun[2] = {1.f, 1.f};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch) {
+        const float gl = ch ? bf_hi(raw.g[i + 3]) : bf_lo(raw.g[i + 3]);
+        const float u = fminf(fast_exp2(-kLog2e * gl), 1e30f);  // exp(-g)
+        float al, ia;
+        if (gs1) {
+          ia = fminf(1.f + u, kInvAlphaMax);  // 1/sigmoid(g) = 1 + exp(-g)
+          al = fmaxf(fast_rcp(1.f + u), kAlphaMin);
+        } else {
+          const float a2 = fmaxf(-gate_scale * fast_log2(1.f + u), -7.5f);
+          al = fast_exp2(a2);
+          ia = fast_exp2(-a2);
+        }
+        if (EDGE && tok0 + i >= s1) { al = 1.f; ia = 1.f; }
+        run[ch] *= al;
+        irun[ch] *= ia;
+        E[i][ch] = run[ch];
+        IE[i][ch] = irun[ch];
+      }
+    }
+    // the other half of the chunk lives 32 lanes away
+    float pre[2], ipre[2], btot[2];
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+      const float ot = __shfl_xor(run[ch], 32);
+      const float oit = __shfl_xor(irun[ch], 32);
+      pre[ch] = th ? ot : 1.f;
+      ipre[ch] = th ? oit : 1.f;
+      btot[ch] = th ? ot * run[ch] : run[ch] * ot;  // first-half product times second-half product
+    }
+    // keys: K' = k/E (in-chunk scores) and Kdec = k E_last/E (state update)
+    float kf[8][2];
+    conv_phi<MODE>(raw.k, wl + ((size_t)GR * D + c0) * 4, kf);
+    unsigned char* kp = smem + G::kKp + tl0 * G::QRS + c0 * 2;
+    float kdv[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch) {
+        E[i][ch] *= pre[ch];
+        const float kk = (EDGE && tok0 + i >= s1) ? 0.f : kf[i][ch];
+        const float kprime = kk * (IE[i][ch] * ipre[ch]);
+        kf[i][ch] = kprime;
+        kdv[i][ch] = kprime * btot[ch];
+      }
+      if (OUTPUT) *reinterpret_cast<uint32_t*>(kp + i * G::QRS) = pack2(kf[i][0], kf[i][1]);
+    }
+    // rows of the channel-major arrays are 8-byte aligned: 8-byte writes
+    unsigned char* kdp = smem + G::kKd + c0 * G::TRS + tl0 * 2;
+    *reinterpret_cast<uint2*>(kdp) = make_uint2(pack2(kdv[0][0], kdv[1][0]), pack2(kdv[2][0], kdv[3][0]));
+    *reinterpret_cast<uint2*>(kdp + 8) = make_uint2(pack2(kdv[4][0], kdv[5][0]), pack2(kdv[6][0], kdv[7][0]));
+    *reinterpret_cast<uint2*>(kdp + G::TRS) = make_uint2(pack2(kdv[0][1], kdv[1][1]), pack2(kdv[2][1], kdv[3][1]));
+    *reinterpret_cast<uint2*>(kdp + G::TRS + 8) = make_uint2(pack2(kdv[4][1], kdv[5][1]), pack2(kdv[6][1], kdv[7][1]));
+    if (th == 0) {
+      float* eb = reinterpret_cast<float*>(smem + G::kEb) + mcw * D + c0;
+      *reinterpret_cast<float2*>(eb) = make_float2(btot[0], btot[1]);
+    }
+    // values, transposed to channel-major (rows past the end were fetched as zero)
+    uint32_t v0[4], v1[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t ra = raw.v[3 + 2 * i], rb = raw.v[4 + 2 * i];
+      v0[i] = __builtin_amdgcn_perm(rb, ra, 0x05040100u);  // low halves:  ra.lo | rb.lo << 16
+      v1[i] = __builtin_amdgcn_perm(rb, ra, 0x07060302u);  // high halves: ra.hi | rb.hi << 16
+    }
+    unsigned char* vp = smem + G::kVt + c0 * G::TRS + tl0 * 2;
+    *reinterpret_cast<uint2*>(vp) = make_uint2(v0[0], v0[1]);
+    *reinterpret_cast<uint2*>(vp + 8) = make_uint2(v0[2], v0[3]);
+    *reinterpret_cast<uint2*>(vp + G::TRS) = make_uint2(v1[0], v1[1]);
+    *reinterpret_cast<uint2*>(vp + G::TRS + 8) = make_uint2(v1[2], v1[3]);
+    if (OUTPUT) {
+      // queries: conv + phi, times E
+#pragma unroll
+      for (int hh = 0; hh < NQ; ++hh) {
+        float qf[8][2];
+        conv_phi<MODE>(raw.q[hh], wl + ((size_t)hh * D + c0) * 4, qf);
+        unsigned char* qp = smem + G::kQp + (hh * G::NTG + tl0) * G::QRS + c0 * 2;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          *reinterpret_cast<uint32_t*>(qp + i * G::QRS) = pack2(qf[i][0] * E[i][0], qf[i][1] * E[i][1]);
+      }
+    }
+  }
+};
+
+template <int D, int GR, int MODE, bool OUTPUT>
+__global__ void __launch_bounds__(256) gla_chunk_kernel(const ChunkArgs a) {
+  using KK = Kernel<D, GR, MODE, OUTPUT>;
+  using G = Geo<D, GR>;
+  constexpr bool CONV = MODE != kPlain;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x;
+  const int w = tid >> 6;   // wave
+  const int l = tid & 63;   // lane
+  const int g4 = l >> 4;    // MFMA lane group
+  const int n = l & 15;     // MFMA row/column within a tile
+  const int seg = blockIdx.x;
+  const int bh = blockIdx.y;
+  const int b = bh / a.Hkv, hk = bh % a.Hkv;
+  const int T = a.T;
+  const int s0 = seg * a.seg_len;
+  const int s1 = min(T, s0 + a.seg_len);
+
+  // load-stage patch of this thread: 8 tokens x 2 channels
+  const int cp = l & 31, th = l >> 5;
+  const int mcw = w / G::CH;                       // chunk of the granule this wave loads
+  const int c0 = 64 * (w % G::CH) + 2 * cp;        // first of the two channels
+  const int tl0 = kChunk * mcw + 8 * th;           // first token of the patch within the granule
+
+  float* wl = reinterpret_cast<float*>(smem + G::kWl);
+  if (CONV) {
+    // conv weights as fp32 [head][channel][4 taps], taps beyond W zero; row GR is the key head
+    const float wscale = MODE == kConvElu ? kLog2e : 1.f;
+    for (int e = tid; e < (GR + 1) * D * 4; e += 256) {
+      const int dl = e & 3, c = (e >> 2) % D, hh = e / (4 * D);
+      float val = 0.f;
+      if (dl < a.W && (OUTPUT || hh == GR)) {
+        const bf16_t* src = hh < GR ? a.wq + ((size_t)(hk * GR + hh) * D + c) * a.W + dl
+                                    : a.wk + ((size_t)hk * D + c) * a.W + dl;
+        val = __uint_as_float((uint32_t)(*src) << 16) * wscale;
+      }
+      wl[e] = val;
+    }
+  }
+
+  // uniform row sources
+  const unsigned kvstride = (unsigned)a.Hkv * D * 2, qstride = (unsigned)a.Hq * D * 2;
+  const RowSrc srcK{(const char*)a.k + ((size_t)b * T * a.Hkv + hk) * D * 2,
+                    (CONV && a.k_halo) ? (const char*)a.k_halo + ((size_t)b * (a.W - 1) * a.Hkv + hk) * D * 2 : nullptr,
+                    kvstride};
+  const RowSrc srcG{(const char*)a.g + ((size_t)b * T * a.Hkv + hk) * D * 2, nullptr, kvstride};
+  const RowSrc srcV{(const char*)a.v + ((size_t)b * T * a.Hkv + hk) * D * 2, nullptr, kvstride};
+  const RowSrc srcQ{(const char*)a.q + ((size_t)b * T * a.Hq + hk * GR) * D * 2,
+                    (CONV && a.q_halo) ? (const char*)a.q_halo + ((size_t)b * (a.W - 1) * a.Hq + hk * GR) * D * 2 : nullptr,
+                    qstride};
+  const unsigned coff = (unsigned)c0 * 2;
+
+  // ---- state in accumulators: Sacc[rt][ct][i] = S[16 rt + 4 g4 + i][16 tile(ct) + n]; ct == CT holds z replicated
+  floatx4 Sacc[G::RT][G::NT];
+  {
+    const float* Sin = nullptr;
+    const float* zin = nullptr;
+    if (OUTPUT) {
+      if (a.nseg > 1) {
+        Sin = a.ws + ((size_t)bh * a.nseg + seg) * G::kSlot;
+        zin = Sin + D * D;
+      } else if (a.S0 != nullptr) {
+        Sin = a.S0 + (size_t)bh * D * D;
+      }
+      if (a.nseg == 1 && a.z0 != nullptr) zin = a.z0 + (size_t)bh * D;
+    }
+#pragma unroll
+    for (int rt = 0; rt < G::RT; ++rt) {
+#pragma unroll
+      for (int ct = 0; ct < G::NT; ++ct) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int c = 16 * rt + 4 * g4 + i;
+          float val = 0.f;
+          if (ct < G::CT) {
+            if (Sin) val = Sin[(size_t)c * D + 16 * (w * G::CT + ct) + n];
+          } else {
+            if (zin) val = zin[c];
+          }
+          Sacc[rt][ct][i] = val;
+        }
+      }
+    }
+  }
+  float dprod[G::RT][4];  // running product of the decay over the segment (first pass only)
+#pragma unroll
+  for (int rt = 0; rt < G::RT; ++rt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) dprod[rt][i] = 1.f;
+
+  const bool gs1 = a.gate_scale == 1.0f;
+  Raw<KK::NQ> raw;
+  KK::fetch(raw, srcK, srcG, srcV, srcQ, s0, s1, tl0, coff, a.W);
+  __syncthreads();  // conv weights are in LDS
+
+  for (int t0 = s0; t0 < s1; t0 += G::NTG) {
+    // =========================== compute stage: registers -> LDS operands ===========================
+    if ((t0 < 3) || (t0 + G::NTG > s1))
+      KK::template compute<true>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, gs1, a.gate_scale);
+    else
+      KK::template compute<false>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, gs1, a.gate_scale);
+    __syncthreads();
+    // next granule's rows travel while the matrix cores work
+    if (t0 + G::NTG < s1) KK::fetch(raw, srcK, srcG, srcV, srcQ, t0 + G::NTG, s1, tl0, coff, a.W);
+
+    // =========================== MFMA stage: 16 tokens at a time ===========================
+#pragma unroll 1
+    for (int mc = 0; mc < G::MCG; ++mc) {
+      const int tq = t0 + kChunk * mc;  // first token of the chunk
+      if (tq >= s1) break;
+      // value fragments: lane (g4, n) holds V[tok 4 g4 .. +3][dv 16 tile + n]; serves as A (V^T) and as B (V)
+      short4v vfrag[G::NT];
+#pragma unroll
+      for (int ct = 0; ct < G::CT; ++ct) {
+        const uint2 r = *reinterpret_cast<const uint2*>(smem + G::kVt + (16 * (w * G::CT + ct) + n) * G::TRS +
+                                                        (kChunk * mc + 4 * g4) * 2);
+        vfrag[ct] = __builtin_bit_cast(short4v, r);
+      }
+      vfrag[G::CT] = short4v{0x3F80, 0x3F80, 0x3F80, 0x3F80};  // ones: the normalizer columns
+
+      if (OUTPUT) {
+        // key fragments of the score product
+        bf16x8 ka[G::KS];
+#pragma unroll
+        for (int ks = 0; ks < G::KS; ++ks) {
+          const unsigned char* p = smem + G::kKp + (kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+          const uint2 lo = *reinterpret_cast<const uint2*>(p);
+          const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
+          ka[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+        }
+        // state as bf16 A-fragments: rows = value columns, k = key channels {4 g4 + i, 16 + 4 g4 + i} of each 32
+        bf16x8 sa[G::NT][G::KS];
+#pragma unroll
+        for (int ct = 0; ct < G::NT; ++ct)
+#pragma unroll
+          for (int ks = 0; ks < G::KS; ++ks) {
+            const floatx4 lo = Sacc[2 * ks][ct], hi = Sacc[2 * ks + 1][ct];
+            sa[ct][ks] = __builtin_bit_cast(
+                bf16x8, make_uint4(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])));
+          }
+#pragma unroll 1
+        for (int hh = 0; hh < GR; ++hh) {
+          bf16x8 qb[G::KS];
+#pragma unroll
+          for (int ks = 0; ks < G::KS; ++ks) {
+            const unsigned char* p =
+                smem + G::kQp + (hh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+            const uint2 lo = *reinterpret_cast<const uint2*>(p);
+            const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
+            qb[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+          }
+          // P^T[key 4 g4 + i][query n]
+          floatx4 pt = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int ks = 0; ks < G::KS; ++ks) pt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qb[ks], pt, 0, 0, 0);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) pt[i] = (4 * g4 + i <= n) ? pt[i] : 0.f;  // causal: key <= query
+          // The weights of the few nearest keys dominate the output, so their bf16 rounding would not
+          // average out: carry P as a bf16 pair (high part + residual), two small MFMAs instead of one.
+          const uint32_t ph0 = pack2(pt[0], pt[1]), ph1 = pack2(pt[2], pt[3]);
+          const short4v pb = __builtin_bit_cast(short4v, make_uint2(ph0, ph1));
+          const short4v pl = __builtin_bit_cast(
+              short4v, make_uint2(pack2(pt[0] - bf_lo(ph0), pt[1] - bf_hi(ph0)), pack2(pt[2] - bf_lo(ph1), pt[3] - bf_hi(ph1))));
+          floatx4 oacc[G::NT];
+#pragma unroll
+          for (int ct = 0; ct < G::NT; ++ct) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pl, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pb, acc, 0, 0, 0);
+#pragma unroll
+            for (int ks = 0; ks < G::KS; ++ks)
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], qb[ks], acc, 0, 0, 0);
+            oacc[ct] = acc;
+          }
+          // o^T[dv 16 tile + 4 g4 + i][query n]; the normalizer tile holds den for query n in every row
+          const int tok = tq + n;
+          const float den = oacc[G::CT][0] + a.eps;
+          const float rden = 1.0f / den;
+          if (tok < s1) {
+            bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * GR + hh) * D;
+#pragma unroll
+            for (int ct = 0; ct < G::CT; ++ct) {
+              const uint2 pk = make_uint2(pack2(oacc[ct][0] * rden, oacc[ct][1] * rden),
+                                          pack2(oacc[ct][2] * rden, oacc[ct][3] * rden));
+              *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
+            }
+            if (a.den_out != nullptr && w == 0 && g4 == 0)
+              a.den_out[((size_t)b * T + tok) * a.Hq + hk * GR + hh] = den;
+          }
+        }
+      }
+      // ---- state update: S <- diag(E_last) S + Kdec^T [V | 1]
+#pragma unroll
+      for (int rt = 0; rt < G::RT; ++rt) {
+        const floatx4 eb = *reinterpret_cast<const floatx4*>(smem + G::kEb + (mc * D + 16 * rt + 4 * g4) * 4);
+        const uint2 kr = *reinterpret_cast<const uint2*>(smem + G::kKd + (16 * rt + n) * G::TRS +
+                                                         (kChunk * mc + 4 * g4) * 2);
+        const short4v kdf = __builtin_bit_cast(short4v, kr);
+        if (!OUTPUT) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) dprod[rt][i] *= eb[i];
+        }
+#pragma unroll
+        for (int ct = 0; ct < G::NT; ++ct) {
+          floatx4 acc = Sacc[rt][ct];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[i] *= eb[i];
+          Sacc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kdf, vfrag[ct], acc, 0, 0, 0);
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- state out: first pass -> workspace slot (S | z | decay); last segment of the output pass -> S_out, z_out
+  float* Sdst = nullptr;
+  float* zdst = nullptr;
+  float* ddst = nullptr;
+  if (!OUTPUT) {
+    Sdst = a.ws + ((size_t)bh * a.nseg + seg) * G::kSlot;
+    zdst = Sdst + D * D;
+    ddst = zdst + D;
+  } else if (seg == a.nseg - 1) {
+    Sdst = a.S_out + (size_t)bh * D * D;
+    zdst = a.z_out + (size_t)bh * D;
+  }
+  if (Sdst != nullptr) {
+#pragma unroll
+    for (int rt = 0; rt < G::RT; ++rt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int c = 16 * rt + 4 * g4 + i;
+#pragma unroll
+        for (int ct = 0; ct < G::CT; ++ct) Sdst[(size_t)c * D + 16 * (w * G::CT + ct) + n] = Sacc[rt][ct][i];
+        if (w == 0 && n == 0) {
+          zdst[c] = Sacc[rt][G::CT][i];
+          if (ddst != nullptr) ddst[c] = dprod[rt][i];
+        }
+      }
+  }
+  // ---- conv cache out: the last W-1 raw rows of [halo ; x] for this workgroup's heads
+  if (OUTPUT && CONV && seg == a.nseg - 1 && a.W > 1) {
+    const int Wm = a.W - 1;
+    for (int e = tid; e < (GR + 1) * Wm * D; e += 256) {
+      const int c = e % D, r = (e / D) % Wm, hh = e / (D * Wm);
+      const bool isq = hh < GR;
+      bf16_t* dst = isq ? a.q_tail : a.k_tail;
+      if (dst == nullptr) continue;
+      const int H = isq ? a.Hq : a.Hkv, head = isq ? hk * GR + hh : hk;
+      const bf16_t* x = isq ? a.q : a.k;
+      const bf16_t* halo = isq ? a.q_halo : a.k_halo;
+      const int src = T - Wm + r;
+      bf16_t val = 0;
+      if (src >= 0) val = x[(((size_t)b * T + src) * H + head) * D + c];
+      else if (halo != nullptr) val = halo[(((size_t)b * Wm + (Wm + src)) * H + head) * D + c];
+      dst[(((size_t)b * Wm + r) * H + head) * D + c] = val;
+    }
+  }
+}
+
+// Turns per-segment contributions into segment start states, in place:
+//   slot[seg] <- state before segment seg;  state <- decay[seg] (.) state + contribution[seg].
+// The loads do not depend on the running state, so they are issued eight segments at a time.
+template <int D>
+__global__ void __launch_bounds__(256) segment_scan_kernel(float* __restrict__ ws, const float* __restrict__ S0,
+                                                          const float* __restrict__ z0, int nseg) {
+  constexpr int kSlot = D * D + 2 * D;
+  constexpr int U = 8;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= D * D + D) return;
+  const int bh = blockIdx.y;
+  const int c = e < D * D ? e / D : e - D * D;
+  float s = 0.f;
+  if (e < D * D) { if (S0) s = S0[(size_t)bh * D * D + e]; }
+  else if (z0) s = z0[(size_t)bh * D + c];
+  float* slot = ws + (size_t)bh * nseg * kSlot;
+  const int last = nseg - 1;  // segments 0 .. last-1 carry contributions
+  int seg = 0;
+  for (; seg + U <= last; seg += U) {
+    float delta[U], dec[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      delta[u] = slot[(size_t)(seg + u) * kSlot + e];
+      dec[u] = slot[(size_t)(seg + u) * kSlot + D * D + D + c];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      slot[(size_t)(seg + u) * kSlot + e] = s;
+      s = fmaf(dec[u], s, delta[u]);
+    }
+  }
+  for (; seg < last; ++seg) {
+    const float delta = slot[(size_t)seg * kSlot + e];
+    const float dec = slot[(size_t)seg * kSlot + D * D + D + c];
+    slot[(size_t)seg * kSlot + e] = s;
+    s = fmaf(dec, s, delta);
+  }
+  slot[(size_t)last * kSlot + e] = s;
+}
+
+template <typename K>
+hipError_t set_lds(K kernel, int bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+extern hipEvent_t g_ev_before, g_ev_after;
+
+template <int D, int GR, int MODE>
+hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
+  using G = Geo<D, GR>;
+  const int heads = a.B * a.Hkv;
+  hipError_t e;
+  if (a.nseg > 1) {
+    auto k1 = gla_chunk_kernel<D, 1, MODE, false>;
+    constexpr int lds1 = Geo<D, 1>::kBytes;
+    static bool set1 = false;
+    if (!set1) {
+      e = set_lds(k1, lds1);
+      if (e != hipSuccess) return e;
+      set1 = true;
+    }
+    hipLaunchKernelGGL(k1, dim3(a.nseg - 1, heads), dim3(256), lds1, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(segment_scan_kernel<D>, dim3((D * D + D + 255) / 256, heads), dim3(256), 0, stream, a.ws, a.S0,
+                       a.z0, a.nseg);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  auto k3 = gla_chunk_kernel<D, GR, MODE, true>;
+  static bool set3 = false;
+  if (!set3) {
+    e = set_lds(k3, G::kBytes);
+    if (e != hipSuccess) return e;
+    set3 = true;
+  }
+  const bool trace = g_ev_before != nullptr && g_ev_after != nullptr;
+  if (trace) {
+    e = hipEventRecord(g_ev_before, stream);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k3, dim3(a.nseg, heads), dim3(256), G::kBytes, stream, a);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (trace) e = hipEventRecord(g_ev_after, stream);
+  return e;
+}
+
+template <int D>
+hipError_t launch_d(const ChunkArgs& a, int group, int mode, hipStream_t stream) {
+#define LAWCAT_CASE(GRV)                                                   \
+  case GRV:                                                                \
+    if (mode == kPlain) return launch_all<D, GRV, kPlain>(a, stream);      \
+    if (mode == kConvId) return launch_all<D, GRV, kConvId>(a, stream);    \
+    return launch_all<D, GRV, kConvElu>(a, stream);
+  switch (group) {
+    LAWCAT_CASE(1)
+    LAWCAT_CASE(2)
+    LAWCAT_CASE(4)
+    default: return hipErrorInvalidValue;
+  }
+#undef LAWCAT_CASE
+}
+
+}  // namespace chunk
+}  // namespace lawcat

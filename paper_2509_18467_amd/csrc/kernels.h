@@ -70,6 +70,8 @@ struct ChunkParams {
   float* den_out;
   float* S_out;
   float* z_out;
+  void* q_tail;  // nullable [B,W-1,Hq,d]  (fuse_conv only)
+  void* k_tail;  // nullable [B,W-1,Hkv,d]
   void* workspace;
   int B, T, Hq, Hkv, d, W;
   int phi;
