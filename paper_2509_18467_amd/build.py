@@ -30,6 +30,7 @@ def build(verbose: bool = False) -> str:
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         extra = PER_FILE_FLAGS.get(src, [])
+        extra = extra + os.environ.get("LAWCAT_EXTRA_FLAGS", "").split()
         cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)

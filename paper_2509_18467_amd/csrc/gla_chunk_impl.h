@@ -168,35 +168,42 @@ struct Kernel {
   static constexpr int NQ = OUTPUT ? GR : 1;
 
   // ---- HBM -> registers: the raw rows of the granule starting at token t0
+  // The fetch is split in two so that fewer registers stay occupied across the MFMA stage:
+  // PART 0 = gate logits, keys, values and the first NQE query heads (issued one stage ahead),
+  // PART 1 = the remaining query heads (issued at the top of the compute stage, they arrive while the
+  // gate and key work runs).
+  static constexpr int NQE = OUTPUT ? (NQ + 1) / 2 : 0;
+  template <int PART>
   __device__ static inline void fetch(Raw<NQ>& raw, const RowSrc& srcK, const RowSrc& srcG, const RowSrc& srcV,
                                       const RowSrc& srcQ, int t0, int s1, int tl0, unsigned coff, int W) {
+    constexpr int H0 = PART == 0 ? 0 : NQE, H1 = PART == 0 ? NQE : (OUTPUT ? NQ : 0);
     const bool edge = (t0 < 3) || (t0 + G::NTG > s1);
     if (!edge) {
-      const unsigned voffkv = (unsigned)tl0 * srcK.stride + coff;
-      load_rows_interior<false>(srcG, t0, voffkv, raw.g);
-      load_rows_interior<CONV>(srcK, t0, voffkv, raw.k);
-      load_rows_interior<false>(srcV, t0, voffkv, raw.v);
-      if (OUTPUT) {
-        const unsigned voffq = (unsigned)tl0 * srcQ.stride + coff;
-#pragma unroll
-        for (int hh = 0; hh < NQ; ++hh) load_rows_interior<CONV>(srcQ, t0, voffq + hh * D * 2, raw.q[hh]);
+      if (PART == 0) {
+        const unsigned voffkv = (unsigned)tl0 * srcK.stride + coff;
+        load_rows_interior<false>(srcG, t0, voffkv, raw.g);
+        load_rows_interior<CONV>(srcK, t0, voffkv, raw.k);
+        load_rows_interior<false>(srcV, t0, voffkv, raw.v);
       }
+      const unsigned voffq = (unsigned)tl0 * srcQ.stride + coff;
+#pragma unroll
+      for (int hh = H0; hh < H1; ++hh) load_rows_interior<CONV>(srcQ, t0, voffq + hh * D * 2, raw.q[hh]);
     } else {
       const int tok0 = t0 + tl0;
-      load_rows_edge<false>(srcG, tok0, s1, 1, coff, raw.g);
-      load_rows_edge<CONV>(srcK, tok0, s1, W, coff, raw.k);
-      load_rows_edge<false>(srcV, tok0, s1, 1, coff, raw.v);
-      if (OUTPUT) {
-#pragma unroll
-        for (int hh = 0; hh < NQ; ++hh) load_rows_edge<CONV>(srcQ, tok0, s1, W, coff + hh * D * 2, raw.q[hh]);
+      if (PART == 0) {
+        load_rows_edge<false>(srcG, tok0, s1, 1, coff, raw.g);
+        load_rows_edge<CONV>(srcK, tok0, s1, W, coff, raw.k);
+        load_rows_edge<false>(srcV, tok0, s1, 1, coff, raw.v);
       }
+#pragma unroll
+      for (int hh = H0; hh < H1; ++hh) load_rows_edge<CONV>(srcQ, tok0, s1, W, coff + hh * D * 2, raw.q[hh]);
     }
   }
 
   // ---- registers -> LDS operands: gate products, conv + phi, scaling by the decay, bf16 packing
-  template <bool EDGE>
+  template <bool EDGE, bool GS1>
   __device__ static inline void compute(const Raw<NQ>& raw, unsigned char* smem, const float* wl, int t0, int s1,
-                                        int tl0, int c0, int mcw, int th, bool gs1, float gate_scale) {
+                                        int tl0, int c0, int mcw, int th, float gate_scale) {
     const int tok0 = t0 + tl0;
     float E[8][2], IE[8][2];
     float run[2] = {1.f, 1.f}, irun[2] = {1.f, 1.f};
@@ -207,7 +214,7 @@ struct Kernel {
         const float gl = ch ? bf_hi(raw.g[i + 3]) : bf_lo(raw.g[i + 3]);
         const float u = fminf(fast_exp2(-kLog2e * gl), 1e30f);  // exp(-g)
         float al, ia;
-        if (gs1) {
+        if (GS1) {
           ia = fminf(1.f + u, kInvAlphaMax);  // 1/sigmoid(g) = 1 + exp(-g)
           al = fmaxf(fast_rcp(1.f + u), kAlphaMin);
         } else {
@@ -232,6 +239,7 @@ struct Kernel {
       ipre[ch] = th ? oit : 1.f;
       btot[ch] = th ? ot * run[ch] : run[ch] * ot;  // first-half product times second-half product
     }
+    __builtin_amdgcn_sched_barrier(0);  // keep the sections apart: bounds live registers
     // keys: K' = k/E (in-chunk scores) and Kdec = k E_last/E (state update)
     float kf[8][2];
     conv_phi<MODE>(raw.k, wl + ((size_t)GR * D + c0) * 4, kf);
@@ -259,6 +267,7 @@ struct Kernel {
       float* eb = reinterpret_cast<float*>(smem + G::kEb) + mcw * D + c0;
       *reinterpret_cast<float2*>(eb) = make_float2(btot[0], btot[1]);
     }
+    __builtin_amdgcn_sched_barrier(0);
     // values, transposed to channel-major (rows past the end were fetched as zero)
     uint32_t v0[4], v1[4];
 #pragma unroll
@@ -276,6 +285,7 @@ struct Kernel {
       // queries: conv + phi, times E
 #pragma unroll
       for (int hh = 0; hh < NQ; ++hh) {
+        __builtin_amdgcn_sched_barrier(0);
         float qf[8][2];
         conv_phi<MODE>(raw.q[hh], wl + ((size_t)hh * D + c0) * 4, qf);
         unsigned char* qp = smem + G::kQp + (hh * G::NTG + tl0) * G::QRS + c0 * 2;
@@ -287,23 +297,33 @@ struct Kernel {
   }
 };
 
-template <int D, int GR, int MODE, bool OUTPUT>
-__global__ void __launch_bounds__(256) gla_chunk_kernel(const ChunkArgs a) {
+// HV = 1: one 256-thread team per workgroup.  HV = 2: two teams of 256 threads, each walking its own
+// segment with its own LDS buffers, run one stage out of phase: while one team is in its VALU-heavy
+// compute stage the other is in its MFMA stage, so the two kinds of work share each SIMD instead of
+// queueing behind the same barrier.
+template <int D, int GR, int MODE, bool OUTPUT, int HV>
+__global__ void __launch_bounds__(256 * HV, D == 64 ? 2 / HV : 1) gla_chunk_kernel(const ChunkArgs a) {
   using KK = Kernel<D, GR, MODE, OUTPUT>;
   using G = Geo<D, GR>;
   constexpr bool CONV = MODE != kPlain;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int tid = threadIdx.x;
-  const int w = tid >> 6;   // wave
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_all[];
+  // team and wave index are wave-uniform: keep them in scalar registers so that everything that
+  // depends on them (stage selection, LDS bases) is uniform control flow and scalar address math
+  const int team = HV > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8)) : 0;
+  unsigned char* smem = smem_all + team * G::kBytes;
+  const int tid = threadIdx.x & 255;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave within the team
   const int l = tid & 63;   // lane
   const int g4 = l >> 4;    // MFMA lane group
   const int n = l & 15;     // MFMA row/column within a tile
-  const int seg = blockIdx.x;
+  const int seg = blockIdx.x * HV + team;
+  const int nseg_pass = OUTPUT ? a.nseg : a.nseg - 1;  // the first pass skips the last segment
+  const bool active = seg < nseg_pass;
   const int bh = blockIdx.y;
   const int b = bh / a.Hkv, hk = bh % a.Hkv;
   const int T = a.T;
   const int s0 = seg * a.seg_len;
-  const int s1 = min(T, s0 + a.seg_len);
+  const int s1 = active ? min(T, s0 + a.seg_len) : s0;
 
   // load-stage patch of this thread: 8 tokens x 2 channels
   const int cp = l & 31, th = l >> 5;
@@ -344,7 +364,7 @@ __global__ void __launch_bounds__(256) gla_chunk_kernel(const ChunkArgs a) {
   {
     const float* Sin = nullptr;
     const float* zin = nullptr;
-    if (OUTPUT) {
+    if (OUTPUT && active) {
       if (a.nseg > 1) {
         Sin = a.ws + ((size_t)bh * a.nseg + seg) * G::kSlot;
         zin = Sin + D * D;
@@ -379,18 +399,40 @@ __global__ void __launch_bounds__(256) gla_chunk_kernel(const ChunkArgs a) {
 
   const bool gs1 = a.gate_scale == 1.0f;
   Raw<KK::NQ> raw;
-  KK::fetch(raw, srcK, srcG, srcV, srcQ, s0, s1, tl0, coff, a.W);
+  if (s0 < s1) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, s0, s1, tl0, coff, a.W);
   __syncthreads();  // conv weights are in LDS
 
-  for (int t0 = s0; t0 < s1; t0 += G::NTG) {
-    // =========================== compute stage: registers -> LDS operands ===========================
-    if ((t0 < 3) || (t0 + G::NTG > s1))
-      KK::template compute<true>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, gs1, a.gate_scale);
-    else
-      KK::template compute<false>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, gs1, a.gate_scale);
-    __syncthreads();
-    // next granule's rows travel while the matrix cores work
-    if (t0 + G::NTG < s1) KK::fetch(raw, srcK, srcG, srcV, srcQ, t0 + G::NTG, s1, tl0, coff, a.W);
+  // Stage sequence of a team: compute(0) mfma(0) compute(1) mfma(1) ..., a barrier after each; team 1
+  // starts one stage late.
+  const int ngran = a.seg_len / G::NTG;
+  const int nstage = 2 * ngran + (HV - 1);
+#ifdef LAWCAT_TIMING
+  long long tc_compute = 0, tc_mfma = 0, tc_barrier = 0, tc_fetchwait = 0;
+  const long long wall0 = wall_clock64();
+#endif
+#pragma unroll 1
+  for (int st = 0; st < nstage; ++st) {
+#ifdef LAWCAT_TIMING
+    const long long tc0 = __builtin_readcyclecounter();
+#endif
+    const int ls = st - team;
+    const int t0 = s0 + (ls >> 1) * G::NTG;
+    if (ls >= 0 && t0 < s1) {
+      if ((ls & 1) == 0) {
+        // =========================== compute stage: registers -> LDS operands ===========================
+        KK::template fetch<1>(raw, srcK, srcG, srcV, srcQ, t0, s1, tl0, coff, a.W);
+        const bool edge = (t0 < 3) || (t0 + G::NTG > s1);
+        if (!edge && gs1)
+          KK::template compute<false, true>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
+        else if (!edge)
+          KK::template compute<false, false>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
+        else if (gs1)
+          KK::template compute<true, true>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
+        else
+          KK::template compute<true, false>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
+      } else {
+        // next granule's rows travel while the matrix cores work
+        if (t0 + G::NTG < s1) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, t0 + G::NTG, s1, tl0, coff, a.W);
 
     // =========================== MFMA stage: 16 tokens at a time ===========================
 #pragma unroll 1
@@ -427,54 +469,85 @@ __global__ void __launch_bounds__(256) gla_chunk_kernel(const ChunkArgs a) {
             sa[ct][ks] = __builtin_bit_cast(
                 bf16x8, make_uint4(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])));
           }
+        // Query heads go through in groups of HP so that the MFMA chains of different heads overlap:
+        // scores and the state term (independent of each other) are issued first, then the masked
+        // scores are packed and the in-chunk term is added.
+        constexpr int HP = GR >= 2 ? 2 : 1;
 #pragma unroll 1
-        for (int hh = 0; hh < GR; ++hh) {
-          bf16x8 qb[G::KS];
+        for (int h0 = 0; h0 < GR; h0 += HP) {
+          bf16x8 qb[HP][G::KS];
 #pragma unroll
-          for (int ks = 0; ks < G::KS; ++ks) {
-            const unsigned char* p =
-                smem + G::kQp + (hh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
-            const uint2 lo = *reinterpret_cast<const uint2*>(p);
-            const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
-            qb[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-          }
+          for (int u = 0; u < HP; ++u)
+#pragma unroll
+            for (int ks = 0; ks < G::KS; ++ks) {
+              const unsigned char* p =
+                  smem + G::kQp + ((h0 + u) * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+              const uint2 lo = *reinterpret_cast<const uint2*>(p);
+              const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
+              qb[u][ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+            }
           // P^T[key 4 g4 + i][query n]
-          floatx4 pt = {0.f, 0.f, 0.f, 0.f};
+          floatx4 pt[HP];
 #pragma unroll
-          for (int ks = 0; ks < G::KS; ++ks) pt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qb[ks], pt, 0, 0, 0);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) pt[i] = (4 * g4 + i <= n) ? pt[i] : 0.f;  // causal: key <= query
-          // The weights of the few nearest keys dominate the output, so their bf16 rounding would not
-          // average out: carry P as a bf16 pair (high part + residual), two small MFMAs instead of one.
-          const uint32_t ph0 = pack2(pt[0], pt[1]), ph1 = pack2(pt[2], pt[3]);
-          const short4v pb = __builtin_bit_cast(short4v, make_uint2(ph0, ph1));
-          const short4v pl = __builtin_bit_cast(
-              short4v, make_uint2(pack2(pt[0] - bf_lo(ph0), pt[1] - bf_hi(ph0)), pack2(pt[2] - bf_lo(ph1), pt[3] - bf_hi(ph1))));
-          floatx4 oacc[G::NT];
-#pragma unroll
-          for (int ct = 0; ct < G::NT; ++ct) {
-            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pl, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pb, acc, 0, 0, 0);
+          for (int u = 0; u < HP; ++u) {
+            pt[u] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < G::KS; ++ks)
-              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], qb[ks], acc, 0, 0, 0);
-            oacc[ct] = acc;
+              pt[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qb[u][ks], pt[u], 0, 0, 0);
           }
+          // state term: o^T[dv][query] = S^T (q (.) E)^T
+          floatx4 oacc[HP][G::NT];
+#pragma unroll
+          for (int u = 0; u < HP; ++u)
+#pragma unroll
+            for (int ct = 0; ct < G::NT; ++ct) {
+              floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+              for (int ks = 0; ks < G::KS; ++ks)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], qb[u][ks], acc, 0, 0, 0);
+              oacc[u][ct] = acc;
+            }
+          // The weights of the few nearest keys dominate the output, so their bf16 rounding would not
+          // average out: carry P as a bf16 pair (high part + residual), two small MFMAs instead of one.
+          short4v pb[HP], pl[HP];
+#pragma unroll
+          for (int u = 0; u < HP; ++u) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) pt[u][i] = (4 * g4 + i <= n) ? pt[u][i] : 0.f;  // causal: key <= query
+            const uint32_t ph0 = pack2(pt[u][0], pt[u][1]), ph1 = pack2(pt[u][2], pt[u][3]);
+            pb[u] = __builtin_bit_cast(short4v, make_uint2(ph0, ph1));
+            pl[u] = __builtin_bit_cast(short4v, make_uint2(pack2(pt[u][0] - bf_lo(ph0), pt[u][1] - bf_hi(ph0)),
+                                                           pack2(pt[u][2] - bf_lo(ph1), pt[u][3] - bf_hi(ph1))));
+          }
+#pragma unroll
+          for (int u = 0; u < HP; ++u)
+#pragma unroll
+            for (int ct = 0; ct < G::NT; ++ct) {
+              floatx4 acc = oacc[u][ct];
+              acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pl[u], acc, 0, 0, 0);
+              acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pb[u], acc, 0, 0, 0);
+              oacc[u][ct] = acc;
+            }
           // o^T[dv 16 tile + 4 g4 + i][query n]; the normalizer tile holds den for query n in every row
           const int tok = tq + n;
-          const float den = oacc[G::CT][0] + a.eps;
-          const float rden = 1.0f / den;
-          if (tok < s1) {
-            bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * GR + hh) * D;
 #pragma unroll
-            for (int ct = 0; ct < G::CT; ++ct) {
-              const uint2 pk = make_uint2(pack2(oacc[ct][0] * rden, oacc[ct][1] * rden),
-                                          pack2(oacc[ct][2] * rden, oacc[ct][3] * rden));
-              *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
+          for (int u = 0; u < HP; ++u) {
+            const int hh = h0 + u;
+            const float den = oacc[u][G::CT][0] + a.eps;
+            const float rden = fast_rcp(den);
+            if (tok < s1) {
+              bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * GR + hh) * D;
+#pragma unroll
+              for (int ct = 0; ct < G::CT; ++ct) {
+                const uint2 pk = make_uint2(pack2(oacc[u][ct][0] * rden, oacc[u][ct][1] * rden),
+                                            pack2(oacc[u][ct][2] * rden, oacc[u][ct][3] * rden));
+                *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
+              }
+#ifndef LAWCAT_TIMING
+              if (a.den_out != nullptr && w == 0 && g4 == 0)
+                a.den_out[((size_t)b * T + tok) * a.Hq + hk * GR + hh] = den;
+#endif
             }
-            if (a.den_out != nullptr && w == 0 && g4 == 0)
-              a.den_out[((size_t)b * T + tok) * a.Hq + hk * GR + hh] = den;
           }
         }
       }
@@ -498,14 +571,30 @@ __global__ void __launch_bounds__(256) gla_chunk_kernel(const ChunkArgs a) {
         }
       }
     }
+      }  // MFMA stage
+    }
+#ifdef LAWCAT_TIMING
+    const long long tc1 = __builtin_readcyclecounter();
+    if (ls >= 0 && t0 < s1) { if ((ls & 1) == 0) tc_compute += tc1 - tc0; else tc_mfma += tc1 - tc0; }
+#endif
     __syncthreads();
+#ifdef LAWCAT_TIMING
+    tc_barrier += __builtin_readcyclecounter() - tc1;
+#endif
   }
+#ifdef LAWCAT_TIMING
+  if (OUTPUT && a.den_out != nullptr && l == 0) {
+    float* dbg = a.den_out + ((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * (4 * HV) + team * 4 + w) * 4;
+    dbg[0] = (float)tc_compute; dbg[1] = (float)tc_mfma; dbg[2] = (float)(wall0 & 0xffffff); dbg[3] = (float)(wall_clock64() & 0xffffff);
+  }
+#endif
 
   // ---- state out: first pass -> workspace slot (S | z | decay); last segment of the output pass -> S_out, z_out
   float* Sdst = nullptr;
   float* zdst = nullptr;
   float* ddst = nullptr;
-  if (!OUTPUT) {
+  if (!active) {
+  } else if (!OUTPUT) {
     Sdst = a.ws + ((size_t)bh * a.nseg + seg) * G::kSlot;
     zdst = Sdst + D * D;
     ddst = zdst + D;
@@ -594,21 +683,21 @@ hipError_t set_lds(K kernel, int bytes) {
 
 extern hipEvent_t g_ev_before, g_ev_after;
 
-template <int D, int GR, int MODE>
+template <int D, int GR, int MODE, int HV>
 hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
   using G = Geo<D, GR>;
   const int heads = a.B * a.Hkv;
   hipError_t e;
   if (a.nseg > 1) {
-    auto k1 = gla_chunk_kernel<D, 1, MODE, false>;
-    constexpr int lds1 = Geo<D, 1>::kBytes;
+    auto k1 = gla_chunk_kernel<D, 1, MODE, false, HV>;
+    constexpr int lds1 = Geo<D, 1>::kBytes * HV;
     static bool set1 = false;
     if (!set1) {
       e = set_lds(k1, lds1);
       if (e != hipSuccess) return e;
       set1 = true;
     }
-    hipLaunchKernelGGL(k1, dim3(a.nseg - 1, heads), dim3(256), lds1, stream, a);
+    hipLaunchKernelGGL(k1, dim3((a.nseg - 1 + HV - 1) / HV, heads), dim3(256 * HV), lds1, stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(segment_scan_kernel<D>, dim3((D * D + D + 255) / 256, heads), dim3(256), 0, stream, a.ws, a.S0,
@@ -616,10 +705,10 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  auto k3 = gla_chunk_kernel<D, GR, MODE, true>;
+  auto k3 = gla_chunk_kernel<D, GR, MODE, true, HV>;
   static bool set3 = false;
   if (!set3) {
-    e = set_lds(k3, G::kBytes);
+    e = set_lds(k3, G::kBytes * HV);
     if (e != hipSuccess) return e;
     set3 = true;
   }
@@ -628,20 +717,20 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
     e = hipEventRecord(g_ev_before, stream);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(k3, dim3(a.nseg, heads), dim3(256), G::kBytes, stream, a);
+  hipLaunchKernelGGL(k3, dim3((a.nseg + HV - 1) / HV, heads), dim3(256 * HV), G::kBytes * HV, stream, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (trace) e = hipEventRecord(g_ev_after, stream);
   return e;
 }
 
-template <int D>
+template <int D, int HV>
 hipError_t launch_d(const ChunkArgs& a, int group, int mode, hipStream_t stream) {
-#define LAWCAT_CASE(GRV)                                                   \
-  case GRV:                                                                \
-    if (mode == kPlain) return launch_all<D, GRV, kPlain>(a, stream);      \
-    if (mode == kConvId) return launch_all<D, GRV, kConvId>(a, stream);    \
-    return launch_all<D, GRV, kConvElu>(a, stream);
+#define LAWCAT_CASE(GRV)                                                       \
+  case GRV:                                                                    \
+    if (mode == kPlain) return launch_all<D, GRV, kPlain, HV>(a, stream);      \
+    if (mode == kConvId) return launch_all<D, GRV, kConvId, HV>(a, stream);    \
+    return launch_all<D, GRV, kConvElu, HV>(a, stream);
   switch (group) {
     LAWCAT_CASE(1)
     LAWCAT_CASE(2)
