@@ -20,7 +20,10 @@ FLAGS = [
 
 # MFMA accumulators in architectural VGPRs (the state is rescaled by plain VALU multiplies every
 # 16 tokens, which AGPR-resident accumulators would have to be copied out for)
-PER_FILE_FLAGS = {"gla_chunk_d64.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+PER_FILE_FLAGS = {
+    "gla_chunk_d64.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "gla_chunk_d128.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+}
 
 
 def build(verbose: bool = False) -> str:

@@ -12,8 +12,8 @@
 // extra value columns that are all ones, so num and den come out of the same MFMAs and the
 // division needs no cross-lane traffic.
 //
-// Parallel decomposition.  One 256-thread workgroup owns one (batch, kv head) and one
-// segment of the sequence, and walks it 16 tokens at a time with the [dk x (dv+16)] state in
+// Parallel decomposition.  One team of d/16 waves (one per 16 value columns) owns one (batch,
+// kv head) and one segment of the sequence, and walks it 16 tokens at a time with the [dk x (dv+16)] state in
 // MFMA accumulators; the query heads of the group share k, v, the decay and the state.  With
 // more than one segment a first pass computes each segment's state contribution and total
 // decay, a small scan turns them into segment start states, and the output pass starts from
@@ -58,11 +58,13 @@ struct ChunkArgs {
 
 template <int D, int GR>
 struct Geo {
+  static constexpr int NW = D / 16;          // waves per team: one per 16 value columns
+  static constexpr int TEAM = 64 * NW;       // threads per team
   static constexpr int CH = D / 64;          // 64-channel slabs per row = waves per 16-token chunk in the load stage
-  static constexpr int NTG = 4096 / D;       // tokens per granule (one load stage of the workgroup)
+  static constexpr int NTG = 64;             // tokens per granule (one load stage of the team)
   static constexpr int MCG = NTG / kChunk;   // chunks per granule
   static constexpr int RT = D / 16;          // 16-row tiles of the state (key channels)
-  static constexpr int CT = D / 64;          // value-column tiles owned by a wave
+  static constexpr int CT = 1;               // value-column tiles owned by a wave
   static constexpr int NT = CT + 1;          // plus the normalizer tile
   static constexpr int KS = D / 32;          // k-steps of a 16x16x32 MFMA over the key channels
   static constexpr int QRS = D * 2 + 8;      // LDS row stride (bytes) of token-major bf16 rows
@@ -168,11 +170,10 @@ struct Kernel {
   static constexpr int NQ = OUTPUT ? GR : 1;
 
   // ---- HBM -> registers: the raw rows of the granule starting at token t0
-  // The fetch is split in two so that fewer registers stay occupied across the MFMA stage:
-  // PART 0 = gate logits, keys, values and the first NQE query heads (issued one stage ahead),
-  // PART 1 = the remaining query heads (issued at the top of the compute stage, they arrive while the
-  // gate and key work runs).
-  static constexpr int NQE = OUTPUT ? (NQ + 1) / 2 : 0;
+  // The fetch is split so that fewer registers stay occupied across the MFMA stage: gate logits,
+  // keys, values and the first NQE query heads are issued one stage ahead (PART 0); the remaining
+  // query heads are fetched inside the compute stage, one head ahead of their use (fetch_head).
+  static constexpr int NQE = (OUTPUT && D == 64) ? (NQ + 1) / 2 : 0;
   template <int PART>
   __device__ static inline void fetch(Raw<NQ>& raw, const RowSrc& srcK, const RowSrc& srcG, const RowSrc& srcV,
                                       const RowSrc& srcQ, int t0, int s1, int tl0, unsigned coff, int W) {
@@ -200,11 +201,24 @@ struct Kernel {
     }
   }
 
+  // One late query head (index >= NQE) of the granule at t0.
+  __device__ static inline void fetch_head(Raw<NQ>& raw, const RowSrc& srcQ, int hh, int t0, int s1, int tl0,
+                                           unsigned coff, int W) {
+    const bool edge = (t0 < 3) || (t0 + G::NTG > s1);
+    if (!edge)
+      load_rows_interior<CONV>(srcQ, t0, (unsigned)tl0 * srcQ.stride + coff + hh * D * 2, raw.q[hh]);
+    else
+      load_rows_edge<CONV>(srcQ, t0 + tl0, s1, W, coff + hh * D * 2, raw.q[hh]);
+  }
+
   // ---- registers -> LDS operands: gate products, conv + phi, scaling by the decay, bf16 packing
   template <bool EDGE, bool GS1>
-  __device__ static inline void compute(const Raw<NQ>& raw, unsigned char* smem, const float* wl, int t0, int s1,
-                                        int tl0, int c0, int mcw, int th, float gate_scale) {
+  __device__ static inline void compute(Raw<NQ>& raw, const RowSrc& srcQ, unsigned coff, int W, unsigned char* smem,
+                                        const float* wl, int t0, int s1, int tl0, int c0, int mcw, int th,
+                                        float gate_scale) {
     const int tok0 = t0 + tl0;
+    // late query heads are fetched one head ahead of their use
+    if (OUTPUT && NQE < NQ) fetch_head(raw, srcQ, NQE, t0, s1, tl0, coff, W);
     float E[8][2], IE[8][2];
     float run[2] = {1.f, 1.f}, irun[2] = {1.f, 1.f};
 #pragma unroll
@@ -286,6 +300,7 @@ struct Kernel {
 #pragma unroll
       for (int hh = 0; hh < NQ; ++hh) {
         __builtin_amdgcn_sched_barrier(0);
+        if (hh >= NQE && hh + 1 < NQ) fetch_head(raw, srcQ, hh + 1, t0, s1, tl0, coff, W);
         float qf[8][2];
         conv_phi<MODE>(raw.q[hh], wl + ((size_t)hh * D + c0) * 4, qf);
         unsigned char* qp = smem + G::kQp + (hh * G::NTG + tl0) * G::QRS + c0 * 2;
@@ -297,21 +312,21 @@ struct Kernel {
   }
 };
 
-// HV = 1: one 256-thread team per workgroup.  HV = 2: two teams of 256 threads, each walking its own
+// HV = 1: one team per workgroup.  HV = 2 (head dim 64 only): two teams, each walking its own
 // segment with its own LDS buffers, run one stage out of phase: while one team is in its VALU-heavy
 // compute stage the other is in its MFMA stage, so the two kinds of work share each SIMD instead of
 // queueing behind the same barrier.
 template <int D, int GR, int MODE, bool OUTPUT, int HV>
-__global__ void __launch_bounds__(256 * HV, D == 64 ? 2 / HV : 1) gla_chunk_kernel(const ChunkArgs a) {
+__global__ void __launch_bounds__((D * 4) * HV, (D == 64 && HV == 1) ? 2 : 1) gla_chunk_kernel(const ChunkArgs a) {
   using KK = Kernel<D, GR, MODE, OUTPUT>;
   using G = Geo<D, GR>;
   constexpr bool CONV = MODE != kPlain;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_all[];
   // team and wave index are wave-uniform: keep them in scalar registers so that everything that
   // depends on them (stage selection, LDS bases) is uniform control flow and scalar address math
-  const int team = HV > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8)) : 0;
+  const int team = HV > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x / G::TEAM)) : 0;
   unsigned char* smem = smem_all + team * G::kBytes;
-  const int tid = threadIdx.x & 255;
+  const int tid = threadIdx.x % G::TEAM;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave within the team
   const int l = tid & 63;   // lane
   const int g4 = l >> 4;    // MFMA lane group
@@ -335,7 +350,7 @@ __global__ void __launch_bounds__(256 * HV, D == 64 ? 2 / HV : 1) gla_chunk_kern
   if (CONV) {
     // conv weights as fp32 [head][channel][4 taps], taps beyond W zero; row GR is the key head
     const float wscale = MODE == kConvElu ? kLog2e : 1.f;
-    for (int e = tid; e < (GR + 1) * D * 4; e += 256) {
+    for (int e = tid; e < (GR + 1) * D * 4; e += G::TEAM) {
       const int dl = e & 3, c = (e >> 2) % D, hh = e / (4 * D);
       float val = 0.f;
       if (dl < a.W && (OUTPUT || hh == GR)) {
@@ -420,16 +435,15 @@ __global__ void __launch_bounds__(256 * HV, D == 64 ? 2 / HV : 1) gla_chunk_kern
     if (ls >= 0 && t0 < s1) {
       if ((ls & 1) == 0) {
         // =========================== compute stage: registers -> LDS operands ===========================
-        KK::template fetch<1>(raw, srcK, srcG, srcV, srcQ, t0, s1, tl0, coff, a.W);
         const bool edge = (t0 < 3) || (t0 + G::NTG > s1);
         if (!edge && gs1)
-          KK::template compute<false, true>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
+          KK::template compute<false, true>(raw, srcQ, coff, a.W, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
         else if (!edge)
-          KK::template compute<false, false>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
+          KK::template compute<false, false>(raw, srcQ, coff, a.W, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
         else if (gs1)
-          KK::template compute<true, true>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
+          KK::template compute<true, true>(raw, srcQ, coff, a.W, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
         else
-          KK::template compute<true, false>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
+          KK::template compute<true, false>(raw, srcQ, coff, a.W, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
       } else {
         // next granule's rows travel while the matrix cores work
         if (t0 + G::NTG < s1) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, t0 + G::NTG, s1, tl0, coff, a.W);
@@ -472,7 +486,7 @@ __global__ void __launch_bounds__(256 * HV, D == 64 ? 2 / HV : 1) gla_chunk_kern
         // Query heads go through in groups of HP so that the MFMA chains of different heads overlap:
         // scores and the state term (independent of each other) are issued first, then the masked
         // scores are packed and the in-chunk term is added.
-        constexpr int HP = GR >= 2 ? 2 : 1;
+        constexpr int HP = (GR >= 2 && D == 64) ? 2 : 1;  // head dim 128 has no registers to spare for pairs
 #pragma unroll 1
         for (int h0 = 0; h0 < GR; h0 += HP) {
           bf16x8 qb[HP][G::KS];
@@ -619,7 +633,7 @@ __global__ void __launch_bounds__(256 * HV, D == 64 ? 2 / HV : 1) gla_chunk_kern
   // ---- conv cache out: the last W-1 raw rows of [halo ; x] for this workgroup's heads
   if (OUTPUT && CONV && seg == a.nseg - 1 && a.W > 1) {
     const int Wm = a.W - 1;
-    for (int e = tid; e < (GR + 1) * Wm * D; e += 256) {
+    for (int e = tid; e < (GR + 1) * Wm * D; e += G::TEAM) {
       const int c = e % D, r = (e / D) % Wm, hh = e / (D * Wm);
       const bool isq = hh < GR;
       bf16_t* dst = isq ? a.q_tail : a.k_tail;
@@ -697,7 +711,7 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
       if (e != hipSuccess) return e;
       set1 = true;
     }
-    hipLaunchKernelGGL(k1, dim3((a.nseg - 1 + HV - 1) / HV, heads), dim3(256 * HV), lds1, stream, a);
+    hipLaunchKernelGGL(k1, dim3((a.nseg - 1 + HV - 1) / HV, heads), dim3(G::TEAM * HV), lds1, stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(segment_scan_kernel<D>, dim3((D * D + D + 255) / 256, heads), dim3(256), 0, stream, a.ws, a.S0,
@@ -717,7 +731,7 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
     e = hipEventRecord(g_ev_before, stream);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(k3, dim3((a.nseg + HV - 1) / HV, heads), dim3(256 * HV), G::kBytes * HV, stream, a);
+  hipLaunchKernelGGL(k3, dim3((a.nseg + HV - 1) / HV, heads), dim3(G::TEAM * HV), G::kBytes * HV, stream, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (trace) e = hipEventRecord(g_ev_after, stream);
