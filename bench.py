@@ -112,14 +112,13 @@ def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0):
             "bytes_step": bytes_step, "nsets": nsets, "host0": host0}
 
 
-def cpu_baseline(wl, host0, feature_map=1, budget_tokens=None):
-    """The fp64 oracle as it stands, on the host cores, on a bounded prefix of the same inputs."""
+def cpu_baseline(wl, host0, feature_map=1, max_tokens=65536):
+    """The fp64 oracle as it stands, on the host cores, on a bounded prefix of the same inputs
+    (the whole sequence up to 65536 tokens: seconds to tens of seconds of CPU work)."""
     from oracle import oracle
 
-    flop_tok = 2 * wl.d * wl.d * (wl.Hq + wl.Hkv)
-    # ~15 s at roughly 1.5 GFLOP/s per thread over min(cores, kv heads) threads
-    threads = min(oracle.max_threads(), wl.B * wl.Hkv)
-    Ts = budget_tokens or int(min(wl.T, max(1024, 15.0 * 1.5e9 * threads / flop_tok)))
+    threads = min(oracle.max_threads(), wl.B * wl.Hkv)  # it parallelizes over (batch, kv head) only
+    Ts = min(wl.T, max_tokens)
     x = {k: (v[:, :Ts] if k in "QKVG" else v) for k, v in host0.items()}
     t0 = time.perf_counter()
     oracle.layer_prefill(x["Q"], x["K"], x["V"], x["G"], x["wq"], x["wk"], feature_map)
@@ -128,12 +127,20 @@ def cpu_baseline(wl, host0, feature_map=1, budget_tokens=None):
             "sample": f"first {Ts} of {wl.T} tokens of the same seeded layer input, all heads, {dt:.1f} s"}
 
 
+def mfma_flops_per_token(wl, chunk=16) -> int:
+    """Useful matrix flops of the chunked form per token: scores and in-chunk product at chunk
+    length C, state term and state update (no padding, no redundancy counted)."""
+    d = wl.d
+    return wl.Hq * (2 * chunk * d + 2 * chunk * d + 2 * d * d) + wl.Hkv * 2 * d * d
+
+
 def read_traffic(name):
     """HBM bytes per output-pass launch from the committed rocprofv3 --pmc summary, if present."""
-    path = os.path.join(ROOT, "profiles", f"traffic_{name}.json")
+    path = os.path.join(ROOT, "profiles", f"output_pass_{name}_hbm_traffic.txt")
     if os.path.exists(path):
-        with open(path) as f:
-            return json.load(f).get("traffic_bytes_per_launch")
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(line.split(":")[1])
     return None
 
 
@@ -183,6 +190,9 @@ def main():
                            "traffic": read_traffic(wl.name), "kernel_ms": r["kernel_ms"],
                            "algorithmic_bytes_per_launch": r["bytes_step"],
                            "whole_step_frac": r["bytes_step"] / (r["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    flops = mfma_flops_per_token(wl) * wl.B * wl.T
+    out["mfma"] = {"useful_flops_per_token": mfma_flops_per_token(wl), "achieved_tflops": flops / (r["ms_per_step"] * 1e-3) / 1e12,
+                   "frac_of_bf16_peak": flops / (r["ms_per_step"] * 1e-3) / 2.5e15}
     if args.sweep:
         sweep = {}
         for name in ("llama1b_8k", "llama1b_32k", "mistral7b_16k", "mistral7b_128k"):

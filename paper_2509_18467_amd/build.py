@@ -10,7 +10,7 @@ CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liblawcat.so")
 SOURCES = ["api.hip", "conv1d.hip", "gla_recurrent.hip", "gla_chunk.hip", "gla_chunk_d64.hip", "gla_chunk_d128.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-# packed-fp32 instructions are switched off on purpose (toolchain notes)
+# packed-fp32 instructions are switched off on purpose: some of their forms have given wrong results on the test machines
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-sanitize", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
