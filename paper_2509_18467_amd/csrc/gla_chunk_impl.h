@@ -71,7 +71,7 @@ struct Geo {
   static constexpr int TRS = NTG * 2 + 8;    // LDS row stride (bytes) of channel-major bf16 rows
   static constexpr int kQp = 0;
   static constexpr int kKp = kQp + GR * NTG * QRS;
-  static constexpr int kKd = kKp + NTG * QRS;
+  static constexpr int kKd = kKp + (GR > 0 ? NTG * QRS : 0);  // GR == 0: the state pass keeps no Q', K' 
   static constexpr int kVt = kKd + D * TRS;
   static constexpr int kEb = kVt + D * TRS;
   static constexpr int kWl = kEb + MCG * D * 4;
@@ -310,6 +310,86 @@ struct Kernel {
       }
     }
   }
+  // ---- state pass only: registers -> LDS operands for S_segment = sum_i (k_i (.) D_i)^T v_i, where D_i is the
+  // decay from token i to the END of the segment.  The segment is walked backwards, so D_i is a product of
+  // (suffix inside the 8-token patch) x (second half of the chunk) x (later chunks of the granule) x (later
+  // granules, `rgran`), all <= 1, and the accumulators never need rescaling.  Contains one team barrier.
+  template <bool EDGE, bool GS1>
+  __device__ static inline void compute_state(const Raw<NQ>& raw, unsigned char* smem, const float* wl, int t0,
+                                              int s1, int tl0, int c0, int mcw, int th, float gate_scale,
+                                              float (&rgran)[2]) {
+    const int tok0 = t0 + tl0;
+    float al[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch) {
+        const float gl = ch ? bf_hi(raw.g[i + 3]) : bf_lo(raw.g[i + 3]);
+        const float u = fminf(fast_exp2(-kLog2e * gl), 1e30f);  // exp(-g)
+        float a1;
+        if (GS1) a1 = fmaxf(fast_rcp(1.f + u), kAlphaMin);
+        else a1 = fast_exp2(fmaxf(-gate_scale * fast_log2(1.f + u), -7.5f));
+        if (EDGE && tok0 + i >= s1) a1 = 1.f;
+        al[i][ch] = a1;
+      }
+    }
+    // exclusive suffix products inside the patch, then to the end of the chunk
+    float suf[8][2], ptot[2];
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+      float r = 1.f;
+#pragma unroll
+      for (int i = 7; i >= 0; --i) { suf[i][ch] = r; r *= al[i][ch]; }
+      ptot[ch] = r;
+    }
+    float btot[2], tail[2];
+#pragma unroll
+    for (int ch = 0; ch < 2; ++ch) {
+      const float ot = __shfl_xor(ptot[ch], 32);
+      tail[ch] = th ? 1.f : ot;               // first half of the chunk is also decayed by the second half
+      btot[ch] = th ? ot * ptot[ch] : ptot[ch] * ot;
+    }
+    float* ebp = reinterpret_cast<float*>(smem + G::kEb);
+    if (th == 0) *reinterpret_cast<float2*>(ebp + mcw * D + c0) = make_float2(btot[0], btot[1]);
+    __syncthreads();
+    // decay of the later chunks of this granule and of everything after the granule
+    float carry[2] = {rgran[0] * tail[0], rgran[1] * tail[1]};
+#pragma unroll
+    for (int m = G::MCG - 1; m >= 0; --m) {
+      const float2 e = *reinterpret_cast<const float2*>(ebp + m * D + c0);
+      if (m > mcw) { carry[0] *= e.x; carry[1] *= e.y; }
+      rgran[0] *= e.x;
+      rgran[1] *= e.y;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    float kf[8][2];
+    conv_phi<MODE>(raw.k, wl + ((size_t)GR * D + c0) * 4, kf);
+    float kdv[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int ch = 0; ch < 2; ++ch) {
+        const float kk = (EDGE && tok0 + i >= s1) ? 0.f : kf[i][ch];
+        kdv[i][ch] = kk * (suf[i][ch] * carry[ch]);
+      }
+    unsigned char* kdp = smem + G::kKd + c0 * G::TRS + tl0 * 2;
+    *reinterpret_cast<uint2*>(kdp) = make_uint2(pack2(kdv[0][0], kdv[1][0]), pack2(kdv[2][0], kdv[3][0]));
+    *reinterpret_cast<uint2*>(kdp + 8) = make_uint2(pack2(kdv[4][0], kdv[5][0]), pack2(kdv[6][0], kdv[7][0]));
+    *reinterpret_cast<uint2*>(kdp + G::TRS) = make_uint2(pack2(kdv[0][1], kdv[1][1]), pack2(kdv[2][1], kdv[3][1]));
+    *reinterpret_cast<uint2*>(kdp + G::TRS + 8) = make_uint2(pack2(kdv[4][1], kdv[5][1]), pack2(kdv[6][1], kdv[7][1]));
+    uint32_t v0[4], v1[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t ra = raw.v[3 + 2 * i], rb = raw.v[4 + 2 * i];
+      v0[i] = __builtin_amdgcn_perm(rb, ra, 0x05040100u);
+      v1[i] = __builtin_amdgcn_perm(rb, ra, 0x07060302u);
+    }
+    unsigned char* vp = smem + G::kVt + c0 * G::TRS + tl0 * 2;
+    *reinterpret_cast<uint2*>(vp) = make_uint2(v0[0], v0[1]);
+    *reinterpret_cast<uint2*>(vp + 8) = make_uint2(v0[2], v0[3]);
+    *reinterpret_cast<uint2*>(vp + G::TRS) = make_uint2(v1[0], v1[1]);
+    *reinterpret_cast<uint2*>(vp + G::TRS + 8) = make_uint2(v1[2], v1[3]);
+  }
 };
 
 // HV = 1: one team per workgroup.  HV = 2 (head dim 64 only): two teams, each walking its own
@@ -317,7 +397,8 @@ struct Kernel {
 // compute stage the other is in its MFMA stage, so the two kinds of work share each SIMD instead of
 // queueing behind the same barrier.
 template <int D, int GR, int MODE, bool OUTPUT, int HV>
-__global__ void __launch_bounds__((D * 4) * HV, (D == 64 && HV == 1) ? 2 : 1) gla_chunk_kernel(const ChunkArgs a) {
+__global__ void __launch_bounds__((D * 4) * HV, OUTPUT ? ((D == 64 && HV == 1) ? 2 : 1) : (D == 64 ? 2 / HV : 1))
+    gla_chunk_kernel(const ChunkArgs a) {
   using KK = Kernel<D, GR, MODE, OUTPUT>;
   using G = Geo<D, GR>;
   constexpr bool CONV = MODE != kPlain;
@@ -406,15 +487,15 @@ __global__ void __launch_bounds__((D * 4) * HV, (D == 64 && HV == 1) ? 2 : 1) gl
       }
     }
   }
-  float dprod[G::RT][4];  // running product of the decay over the segment (first pass only)
-#pragma unroll
-  for (int rt = 0; rt < G::RT; ++rt)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) dprod[rt][i] = 1.f;
+  float rgran[2] = {1.f, 1.f};  // state pass: decay of everything after the current granule, this lane's 2 channels
 
   const bool gs1 = a.gate_scale == 1.0f;
   Raw<KK::NQ> raw;
-  if (s0 < s1) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, s0, s1, tl0, coff, a.W);
+  // the output pass walks its segment forwards, the state pass backwards (see compute_state)
+  const int nseg_gran = (s1 - s0 + G::NTG - 1) / G::NTG;
+  const int tfirst = OUTPUT ? s0 : s0 + (nseg_gran - 1) * G::NTG;
+  const int tstep = OUTPUT ? G::NTG : -G::NTG;
+  if (s0 < s1) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, tfirst, s1, tl0, coff, a.W);
   __syncthreads();  // conv weights are in LDS
 
   // Stage sequence of a team: compute(0) mfma(0) compute(1) mfma(1) ..., a barrier after each; team 1
@@ -431,12 +512,21 @@ __global__ void __launch_bounds__((D * 4) * HV, (D == 64 && HV == 1) ? 2 : 1) gl
     const long long tc0 = __builtin_readcyclecounter();
 #endif
     const int ls = st - team;
-    const int t0 = s0 + (ls >> 1) * G::NTG;
-    if (ls >= 0 && t0 < s1) {
+    const int t0 = tfirst + (ls >> 1) * tstep;
+    if (ls >= 0 && (ls >> 1) < nseg_gran) {
       if ((ls & 1) == 0) {
         // =========================== compute stage: registers -> LDS operands ===========================
         const bool edge = (t0 < 3) || (t0 + G::NTG > s1);
-        if (!edge && gs1)
+        if (!OUTPUT) {
+          if (!edge && gs1)
+            KK::template compute_state<false, true>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale, rgran);
+          else if (!edge)
+            KK::template compute_state<false, false>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale, rgran);
+          else if (gs1)
+            KK::template compute_state<true, true>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale, rgran);
+          else
+            KK::template compute_state<true, false>(raw, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale, rgran);
+        } else if (!edge && gs1)
           KK::template compute<false, true>(raw, srcQ, coff, a.W, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
         else if (!edge)
           KK::template compute<false, false>(raw, srcQ, coff, a.W, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
@@ -446,7 +536,7 @@ __global__ void __launch_bounds__((D * 4) * HV, (D == 64 && HV == 1) ? 2 : 1) gl
           KK::template compute<true, false>(raw, srcQ, coff, a.W, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
       } else {
         // next granule's rows travel while the matrix cores work
-        if (t0 + G::NTG < s1) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, t0 + G::NTG, s1, tl0, coff, a.W);
+        if ((ls >> 1) + 1 < nseg_gran) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, t0 + tstep, s1, tl0, coff, a.W);
 
     // =========================== MFMA stage: 16 tokens at a time ===========================
 #pragma unroll 1
@@ -568,19 +658,18 @@ __global__ void __launch_bounds__((D * 4) * HV, (D == 64 && HV == 1) ? 2 : 1) gl
       // ---- state update: S <- diag(E_last) S + Kdec^T [V | 1]
 #pragma unroll
       for (int rt = 0; rt < G::RT; ++rt) {
-        const floatx4 eb = *reinterpret_cast<const floatx4*>(smem + G::kEb + (mc * D + 16 * rt + 4 * g4) * 4);
         const uint2 kr = *reinterpret_cast<const uint2*>(smem + G::kKd + (16 * rt + n) * G::TRS +
                                                          (kChunk * mc + 4 * g4) * 2);
         const short4v kdf = __builtin_bit_cast(short4v, kr);
-        if (!OUTPUT) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) dprod[rt][i] *= eb[i];
-        }
+        floatx4 eb = {1.f, 1.f, 1.f, 1.f};
+        if (OUTPUT) eb = *reinterpret_cast<const floatx4*>(smem + G::kEb + (mc * D + 16 * rt + 4 * g4) * 4);
 #pragma unroll
         for (int ct = 0; ct < G::NT; ++ct) {
           floatx4 acc = Sacc[rt][ct];
+          if (OUTPUT) {  // the state pass pre-decays its operands to the end of the segment instead
 #pragma unroll
-          for (int i = 0; i < 4; ++i) acc[i] *= eb[i];
+            for (int i = 0; i < 4; ++i) acc[i] *= eb[i];
+          }
           Sacc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kdf, vfrag[ct], acc, 0, 0, 0);
         }
       }
@@ -624,11 +713,10 @@ __global__ void __launch_bounds__((D * 4) * HV, (D == 64 && HV == 1) ? 2 : 1) gl
         const int c = 16 * rt + 4 * g4 + i;
 #pragma unroll
         for (int ct = 0; ct < G::CT; ++ct) Sdst[(size_t)c * D + 16 * (w * G::CT + ct) + n] = Sacc[rt][ct][i];
-        if (w == 0 && n == 0) {
-          zdst[c] = Sacc[rt][G::CT][i];
-          if (ddst != nullptr) ddst[c] = dprod[rt][i];
-        }
+        if (w == 0 && n == 0) zdst[c] = Sacc[rt][G::CT][i];
       }
+    // total decay of the segment: the waves that loaded chunk 0 hold it for their two channels
+    if (ddst != nullptr && mcw == 0 && th == 0) *reinterpret_cast<float2*>(ddst + c0) = make_float2(rgran[0], rgran[1]);
   }
   // ---- conv cache out: the last W-1 raw rows of [halo ; x] for this workgroup's heads
   if (OUTPUT && CONV && seg == a.nseg - 1 && a.W > 1) {
@@ -703,15 +791,16 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
   const int heads = a.B * a.Hkv;
   hipError_t e;
   if (a.nseg > 1) {
-    auto k1 = gla_chunk_kernel<D, 1, MODE, false, HV>;
-    constexpr int lds1 = Geo<D, 1>::kBytes * HV;
+    // GR = 0: key side only.  Always one team per workgroup: its compute stage holds a barrier of its own.
+    auto k1 = gla_chunk_kernel<D, 0, MODE, false, 1>;
+    constexpr int lds1 = Geo<D, 0>::kBytes;
     static bool set1 = false;
     if (!set1) {
       e = set_lds(k1, lds1);
       if (e != hipSuccess) return e;
       set1 = true;
     }
-    hipLaunchKernelGGL(k1, dim3((a.nseg - 1 + HV - 1) / HV, heads), dim3(G::TEAM * HV), lds1, stream, a);
+    hipLaunchKernelGGL(k1, dim3(a.nseg - 1, heads), dim3(G::TEAM), lds1, stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(segment_scan_kernel<D>, dim3((D * D + D + 255) / 256, heads), dim3(256), 0, stream, a.ws, a.S0,
