@@ -27,8 +27,10 @@ ChunkPlan make_chunk_plan(int B, int T, int Hkv, int d, int carry_mode, int segm
   } else if (segment > 0) {
     seg_len = segment;
   } else {
-    // enough workgroups for two per compute unit, segments no shorter than 128 tokens
-    const int want = (512 + heads - 1) / heads;
+    // enough workgroups to fill 256 compute units once (two 4-wave teams per unit at head dim 64, one
+    // 8-wave team at 128), segments no shorter than 128 tokens
+    const int slots = d == 64 ? 512 : 256;
+    const int want = (slots + heads - 1) / heads;
     seg_len = (T + want - 1) / want;
     seg_len = (seg_len + 63) / 64 * 64;
     if (seg_len < 128) seg_len = 128;

@@ -740,42 +740,68 @@ __global__ void __launch_bounds__((D * 4) * HV, OUTPUT ? ((D == 64 && HV == 1) ?
 
 // Turns per-segment contributions into segment start states, in place:
 //   slot[seg] <- state before segment seg;  state <- decay[seg] (.) state + contribution[seg].
-// The loads do not depend on the running state, so they are issued eight segments at a time.
+// The recurrence is linear, so the segments are cut into 8 groups: 8 threads per state element each
+// reduce their group to (product of decays, contribution from a zero start), the eight pairs are
+// combined through LDS, and each thread replays its group from its true start.  All loads of a
+// group are independent of the running state and issued together.
 template <int D>
 __global__ void __launch_bounds__(256) segment_scan_kernel(float* __restrict__ ws, const float* __restrict__ S0,
                                                           const float* __restrict__ z0, int nseg) {
   constexpr int kSlot = D * D + 2 * D;
-  constexpr int U = 8;
-  const int e = blockIdx.x * 256 + threadIdx.x;
-  if (e >= D * D + D) return;
+  constexpr int NG = 8, U = 8;
+  __shared__ float agg_a[NG][32], agg_x[NG][32];
+  const int el = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int e = blockIdx.x * 32 + el;
+  const bool live = e < D * D + D;
   const int bh = blockIdx.y;
-  const int c = e < D * D ? e / D : e - D * D;
-  float s = 0.f;
-  if (e < D * D) { if (S0) s = S0[(size_t)bh * D * D + e]; }
-  else if (z0) s = z0[(size_t)bh * D + c];
+  const int c = !live ? 0 : (e < D * D ? e / D : e - D * D);
+  const int ec = live ? e : 0;
   float* slot = ws + (size_t)bh * nseg * kSlot;
-  const int last = nseg - 1;  // segments 0 .. last-1 carry contributions
-  int seg = 0;
-  for (; seg + U <= last; seg += U) {
+  const int last = nseg - 1;                 // segments 0 .. last-1 carry contributions
+  const int spg = (last + NG - 1) / NG;      // segments per group
+  const int sb = min(last, grp * spg), se = min(last, sb + spg);
+  // phase 1: (A, X) of the group from a zero start
+  float A = 1.f, X = 0.f;
+  for (int seg = sb; seg < se; seg += U) {
     float delta[U], dec[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      delta[u] = slot[(size_t)(seg + u) * kSlot + e];
-      dec[u] = slot[(size_t)(seg + u) * kSlot + D * D + D + c];
+      const int sg = min(seg + u, se - 1);
+      delta[u] = slot[(size_t)sg * kSlot + ec];
+      dec[u] = slot[(size_t)sg * kSlot + D * D + D + c];
     }
 #pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (seg + u < se) { X = fmaf(dec[u], X, delta[u]); A *= dec[u]; }
+  }
+  agg_a[grp][el] = A;
+  agg_x[grp][el] = X;
+  __syncthreads();
+  // phase 2: true start of the group
+  float st = 0.f;
+  if (live) {
+    if (e < D * D) { if (S0) st = S0[(size_t)bh * D * D + e]; }
+    else if (z0) st = z0[(size_t)bh * D + c];
+  }
+  for (int j = 0; j < grp; ++j) st = fmaf(agg_a[j][el], st, agg_x[j][el]);
+  // phase 3: replay, writing start states over the contributions
+  for (int seg = sb; seg < se; seg += U) {
+    float delta[U], dec[U];
+#pragma unroll
     for (int u = 0; u < U; ++u) {
-      slot[(size_t)(seg + u) * kSlot + e] = s;
-      s = fmaf(dec[u], s, delta[u]);
+      const int sg = min(seg + u, se - 1);
+      delta[u] = slot[(size_t)sg * kSlot + ec];
+      dec[u] = slot[(size_t)sg * kSlot + D * D + D + c];
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (seg + u < se) {
+        if (live) slot[(size_t)(seg + u) * kSlot + e] = st;
+        st = fmaf(dec[u], st, delta[u]);
+      }
   }
-  for (; seg < last; ++seg) {
-    const float delta = slot[(size_t)seg * kSlot + e];
-    const float dec = slot[(size_t)seg * kSlot + D * D + D + c];
-    slot[(size_t)seg * kSlot + e] = s;
-    s = fmaf(dec, s, delta);
-  }
-  slot[(size_t)last * kSlot + e] = s;
+  // the group that ends at the last contribution also owns the start state of the last segment
+  if (live && se == last && sb < se) slot[(size_t)last * kSlot + e] = st;
 }
 
 template <typename K>
@@ -803,7 +829,7 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL(k1, dim3(a.nseg - 1, heads), dim3(G::TEAM), lds1, stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(segment_scan_kernel<D>, dim3((D * D + D + 255) / 256, heads), dim3(256), 0, stream, a.ws, a.S0,
+    hipLaunchKernelGGL(segment_scan_kernel<D>, dim3((D * D + D + 31) / 32, heads), dim3(256), 0, stream, a.ws, a.S0,
                        a.z0, a.nseg);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
