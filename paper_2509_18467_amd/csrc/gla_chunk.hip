@@ -1,13 +1,11 @@
 // Host side of the bf16 matrix-core prefill: segment plan, workspace size, dispatch to the
 // per-head-dimension translation units.
-#include <cstdlib>
-
 #include "gla_chunk_impl.h"
 
 namespace lawcat {
 namespace chunk {
 hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
-hipError_t launch_d64(const ChunkArgs& a, int group, int mode, int teams, hipStream_t stream);
+hipError_t launch_d64(const ChunkArgs& a, int group, int mode, hipStream_t stream);
 hipError_t launch_d128(const ChunkArgs& a, int group, int mode, hipStream_t stream);
 }  // namespace chunk
 
@@ -54,12 +52,7 @@ hipError_t launch_gla_chunk(const ChunkParams& p, hipStream_t stream) {
   a.gate_scale = p.gate_scale; a.eps = p.eps;
   const int group = p.Hq / p.Hkv;
   const int mode = !p.fuse_conv ? chunk::kPlain : (p.phi == 1 ? chunk::kConvElu : chunk::kConvId);
-  // tuning override: LAWCAT_TEAMS=1|2 picks one or two phase-shifted teams per workgroup (head dim 64)
-  static const int teams = [] {
-    const char* e = getenv("LAWCAT_TEAMS");
-    return (e != nullptr && e[0] == '2') ? 2 : 1;
-  }();
-  return p.d == 64 ? chunk::launch_d64(a, group, mode, teams, stream) : chunk::launch_d128(a, group, mode, stream);
+  return p.d == 64 ? chunk::launch_d64(a, group, mode, stream) : chunk::launch_d128(a, group, mode, stream);
 }
 
 }  // namespace lawcat

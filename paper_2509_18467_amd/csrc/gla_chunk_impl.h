@@ -75,7 +75,8 @@ struct Geo {
   static constexpr int kVt = kKd + D * TRS;
   static constexpr int kEb = kVt + D * TRS;
   static constexpr int kWl = kEb + MCG * D * 4;
-  static constexpr int kBytes = kWl + (GR + 1) * D * 16;
+  static constexpr int kPs = kWl + (GR + 1) * D * 16;   // shared scores: [2 buffers][GR heads][hi, lo][64 lanes] x 8 B
+  static constexpr int kBytes = kPs + 2 * GR * 2 * 512;
   static constexpr int kSlot = D * D + 2 * D;  // floats per workspace slot: S | z | decay
 };
 
@@ -554,14 +555,34 @@ __global__ void __launch_bounds__((D * 4) * HV, OUTPUT ? ((D == 64 && HV == 1) ?
       vfrag[G::CT] = short4v{0x3F80, 0x3F80, 0x3F80, 0x3F80};  // ones: the normalizer columns
 
       if (OUTPUT) {
-        // key fragments of the score product
-        bf16x8 ka[G::KS];
+        // ---- scores: wave w computes P^T = K' Q'^T for query head w % GR only and shares it through LDS
+        const int myh = w % GR;
+        {
+          floatx4 pt = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < G::KS; ++ks) {
-          const unsigned char* p = smem + G::kKp + (kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
-          const uint2 lo = *reinterpret_cast<const uint2*>(p);
-          const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
-          ka[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+          for (int ks = 0; ks < G::KS; ++ks) {
+            const unsigned char* pk = smem + G::kKp + (kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+            const unsigned char* pq = smem + G::kQp + (myh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+            const uint2 klo = *reinterpret_cast<const uint2*>(pk), khi = *reinterpret_cast<const uint2*>(pk + 32);
+            const uint2 qlo = *reinterpret_cast<const uint2*>(pq), qhi = *reinterpret_cast<const uint2*>(pq + 32);
+            pt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, make_uint4(klo.x, klo.y, khi.x, khi.y)),
+                __builtin_bit_cast(bf16x8, make_uint4(qlo.x, qlo.y, qhi.x, qhi.y)), pt, 0, 0, 0);
+          }
+          // P^T[key 4 g4 + i][query n], causal: key <= query
+#pragma unroll
+          for (int i = 0; i < 4; ++i) pt[i] = (4 * g4 + i <= n) ? pt[i] : 0.f;
+          // The weights of the few nearest keys dominate the output, so their bf16 rounding would not
+          // average out: carry P as a bf16 pair (high part + residual), two small MFMAs instead of one.
+          const uint32_t ph0 = pack2(pt[0], pt[1]), ph1 = pack2(pt[2], pt[3]);
+          const uint2 hi2 = make_uint2(ph0, ph1);
+          const uint2 lo2 = make_uint2(pack2(pt[0] - bf_lo(ph0), pt[1] - bf_hi(ph0)),
+                                       pack2(pt[2] - bf_lo(ph1), pt[3] - bf_hi(ph1)));
+          if (w < GR) {
+            unsigned char* ps = smem + G::kPs + (((mc & 1) * GR + myh) * 2) * 512 + l * 8;
+            *reinterpret_cast<uint2*>(ps) = hi2;
+            *reinterpret_cast<uint2*>(ps + 512) = lo2;
+          }
         }
         // state as bf16 A-fragments: rows = value columns, k = key channels {4 g4 + i, 16 + 4 g4 + i} of each 32
         bf16x8 sa[G::NT][G::KS];
@@ -573,15 +594,15 @@ __global__ void __launch_bounds__((D * 4) * HV, OUTPUT ? ((D == 64 && HV == 1) ?
             sa[ct][ks] = __builtin_bit_cast(
                 bf16x8, make_uint4(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])));
           }
-        // Query heads go through in groups of HP so that the MFMA chains of different heads overlap:
-        // scores and the state term (independent of each other) are issued first, then the masked
-        // scores are packed and the in-chunk term is added.
+        __syncthreads();  // scores of this chunk are in LDS (double-buffered by chunk parity)
+        // Query heads go through in groups of HP so that the MFMA chains of different heads overlap.
         constexpr int HP = (GR >= 2 && D == 64) ? 2 : 1;  // head dim 128 has no registers to spare for pairs
 #pragma unroll 1
         for (int h0 = 0; h0 < GR; h0 += HP) {
           bf16x8 qb[HP][G::KS];
+          short4v pb[HP], pl[HP];
 #pragma unroll
-          for (int u = 0; u < HP; ++u)
+          for (int u = 0; u < HP; ++u) {
 #pragma unroll
             for (int ks = 0; ks < G::KS; ++ks) {
               const unsigned char* p =
@@ -590,16 +611,11 @@ __global__ void __launch_bounds__((D * 4) * HV, OUTPUT ? ((D == 64 && HV == 1) ?
               const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
               qb[u][ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
             }
-          // P^T[key 4 g4 + i][query n]
-          floatx4 pt[HP];
-#pragma unroll
-          for (int u = 0; u < HP; ++u) {
-            pt[u] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < G::KS; ++ks)
-              pt[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks], qb[u][ks], pt[u], 0, 0, 0);
+            const unsigned char* ps = smem + G::kPs + (((mc & 1) * GR + h0 + u) * 2) * 512 + l * 8;
+            pb[u] = __builtin_bit_cast(short4v, *reinterpret_cast<const uint2*>(ps));
+            pl[u] = __builtin_bit_cast(short4v, *reinterpret_cast<const uint2*>(ps + 512));
           }
-          // state term: o^T[dv][query] = S^T (q (.) E)^T
+          // o^T[dv][query] = S^T (q (.) E)^T + [V|1]^T P^T
           floatx4 oacc[HP][G::NT];
 #pragma unroll
           for (int u = 0; u < HP; ++u)
@@ -609,30 +625,11 @@ __global__ void __launch_bounds__((D * 4) * HV, OUTPUT ? ((D == 64 && HV == 1) ?
 #pragma unroll
               for (int ks = 0; ks < G::KS; ++ks)
                 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], qb[u][ks], acc, 0, 0, 0);
-              oacc[u][ct] = acc;
-            }
-          // The weights of the few nearest keys dominate the output, so their bf16 rounding would not
-          // average out: carry P as a bf16 pair (high part + residual), two small MFMAs instead of one.
-          short4v pb[HP], pl[HP];
-#pragma unroll
-          for (int u = 0; u < HP; ++u) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) pt[u][i] = (4 * g4 + i <= n) ? pt[u][i] : 0.f;  // causal: key <= query
-            const uint32_t ph0 = pack2(pt[u][0], pt[u][1]), ph1 = pack2(pt[u][2], pt[u][3]);
-            pb[u] = __builtin_bit_cast(short4v, make_uint2(ph0, ph1));
-            pl[u] = __builtin_bit_cast(short4v, make_uint2(pack2(pt[u][0] - bf_lo(ph0), pt[u][1] - bf_hi(ph0)),
-                                                           pack2(pt[u][2] - bf_lo(ph1), pt[u][3] - bf_hi(ph1))));
-          }
-#pragma unroll
-          for (int u = 0; u < HP; ++u)
-#pragma unroll
-            for (int ct = 0; ct < G::NT; ++ct) {
-              floatx4 acc = oacc[u][ct];
               acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pl[u], acc, 0, 0, 0);
               acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pb[u], acc, 0, 0, 0);
               oacc[u][ct] = acc;
             }
-          // o^T[dv 16 tile + 4 g4 + i][query n]; the normalizer tile holds den for query n in every row
+          // the normalizer tile holds den for query n in every row
           const int tok = tq + n;
 #pragma unroll
           for (int u = 0; u < HP; ++u) {
