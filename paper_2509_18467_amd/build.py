@@ -18,22 +18,13 @@ FLAGS = [
 ]
 
 
-# MFMA accumulators in architectural VGPRs (the state is rescaled by plain VALU multiplies every
-# 16 tokens, which AGPR-resident accumulators would have to be copied out for)
-PER_FILE_FLAGS = {
-    "gla_chunk_d64.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
-    "gla_chunk_d128.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
-}
-
-
 def build(verbose: bool = False) -> str:
     objdir = os.path.join(_HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
 
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        extra = PER_FILE_FLAGS.get(src, [])
-        extra = extra + os.environ.get("LAWCAT_EXTRA_FLAGS", "").split()
+        extra = os.environ.get("LAWCAT_EXTRA_FLAGS", "").split()
         cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
