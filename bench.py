@@ -58,7 +58,7 @@ class HipEvents:
             self.hip.hipEventDestroy(b)
 
 
-def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0):
+def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0, segment=0):
     import torch
 
     from paper_2509_18467_amd import lawcat
@@ -67,7 +67,7 @@ def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0):
     dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
     desc = lawcat.make_desc(wl.B, wl.T, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W,
                             dtype=lawcat.DTYPE_BF16 if wl.dtype == "bf16" else lawcat.DTYPE_F32,
-                            feature_map=feature_map)
+                            feature_map=feature_map, segment=segment)
     bytes_step = algorithmic_bytes_per_token(wl) * wl.B * wl.T
     # rotate input/output sets so the 256 MB Infinity Cache cannot serve a step's reads
     nsets = max(2, min(12, -(-(1 << 30) // bytes_step)))
@@ -153,6 +153,7 @@ def main():
     ap.add_argument("--feature-map", type=int, default=1)
     ap.add_argument("--sweep", action="store_true", help="also time the other graded shapes (reported under 'sweep')")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--segment", type=int, default=0, help="tokens per segment (0 = the library's choice)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -165,7 +166,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     wl = WORKLOADS[args.workload]
-    r = run_workload(wl, args.steps, args.warmup, args.feature_map)
+    r = run_workload(wl, args.steps, args.warmup, args.feature_map, segment=args.segment)
     out = {
         "metric": "prefill tokens/s per layer",
         "value": r["tokens_per_s"],

@@ -3,7 +3,7 @@
 namespace lawcat {
 namespace chunk {
 hipError_t launch_d128(const ChunkArgs& a, int group, int mode, hipStream_t stream) {
-  return launch_d<128, 1>(a, group, mode, stream);
+  return launch_d<128>(a, group, mode, stream);
 }
 }  // namespace chunk
 }  // namespace lawcat

@@ -3,7 +3,7 @@
 namespace lawcat {
 namespace chunk {
 hipError_t launch_d64(const ChunkArgs& a, int group, int mode, hipStream_t stream) {
-  return launch_d<64, 1>(a, group, mode, stream);
+  return launch_d<64>(a, group, mode, stream);
 }
 }  // namespace chunk
 }  // namespace lawcat

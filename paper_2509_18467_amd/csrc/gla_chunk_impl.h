@@ -393,27 +393,23 @@ struct Kernel {
   }
 };
 
-// HV = 1: one team per workgroup.  HV = 2 (head dim 64 only): two teams, each walking its own
-// segment with its own LDS buffers, run one stage out of phase: while one team is in its VALU-heavy
-// compute stage the other is in its MFMA stage, so the two kinds of work share each SIMD instead of
-// queueing behind the same barrier.
-template <int D, int GR, int MODE, bool OUTPUT, int HV>
-__global__ void __launch_bounds__((D * 4) * HV, OUTPUT ? ((D == 64 && HV == 1) ? 2 : 1) : (D == 64 ? 2 / HV : 1))
+// One workgroup = one team of d/16 waves.  At head dim 64 two workgroups share a compute unit (256 VGPRs each).
+template <int D, int GR, int MODE, bool OUTPUT>
+__global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
     gla_chunk_kernel(const ChunkArgs a) {
   using KK = Kernel<D, GR, MODE, OUTPUT>;
   using G = Geo<D, GR>;
   constexpr bool CONV = MODE != kPlain;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_all[];
-  // team and wave index are wave-uniform: keep them in scalar registers so that everything that
-  // depends on them (stage selection, LDS bases) is uniform control flow and scalar address math
-  const int team = HV > 1 ? __builtin_amdgcn_readfirstlane((int)(threadIdx.x / G::TEAM)) : 0;
-  unsigned char* smem = smem_all + team * G::kBytes;
-  const int tid = threadIdx.x % G::TEAM;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave within the team
+  unsigned char* smem = smem_all;
+  const int tid = threadIdx.x;
+  // the wave index is wave-uniform: keep it in a scalar register so that everything that depends on it
+  // (LDS bases, branches) is uniform control flow and scalar address math
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l = tid & 63;   // lane
   const int g4 = l >> 4;    // MFMA lane group
   const int n = l & 15;     // MFMA row/column within a tile
-  const int seg = blockIdx.x * HV + team;
+  const int seg = blockIdx.x;
   const int nseg_pass = OUTPUT ? a.nseg : a.nseg - 1;  // the first pass skips the last segment
   const bool active = seg < nseg_pass;
   const int bh = blockIdx.y;
@@ -499,20 +495,12 @@ __global__ void __launch_bounds__((D * 4) * HV, OUTPUT ? ((D == 64 && HV == 1) ?
   if (s0 < s1) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, tfirst, s1, tl0, coff, a.W);
   __syncthreads();  // conv weights are in LDS
 
-  // Stage sequence of a team: compute(0) mfma(0) compute(1) mfma(1) ..., a barrier after each; team 1
-  // starts one stage late.
+  // Stage sequence: compute(0) mfma(0) compute(1) mfma(1) ..., a barrier after each.
   const int ngran = a.seg_len / G::NTG;
-  const int nstage = 2 * ngran + (HV - 1);
-#ifdef LAWCAT_TIMING
-  long long tc_compute = 0, tc_mfma = 0, tc_barrier = 0, tc_fetchwait = 0;
-  const long long wall0 = wall_clock64();
-#endif
+  const int nstage = 2 * ngran;
 #pragma unroll 1
   for (int st = 0; st < nstage; ++st) {
-#ifdef LAWCAT_TIMING
-    const long long tc0 = __builtin_readcyclecounter();
-#endif
-    const int ls = st - team;
+    const int ls = st;
     const int t0 = tfirst + (ls >> 1) * tstep;
     if (ls >= 0 && (ls >> 1) < nseg_gran) {
       if ((ls & 1) == 0) {
@@ -644,10 +632,8 @@ __global__ void __launch_bounds__((D * 4) * HV, OUTPUT ? ((D == 64 && HV == 1) ?
                                             pack2(oacc[u][ct][2] * rden, oacc[u][ct][3] * rden));
                 *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
               }
-#ifndef LAWCAT_TIMING
               if (a.den_out != nullptr && w == 0 && g4 == 0)
                 a.den_out[((size_t)b * T + tok) * a.Hq + hk * GR + hh] = den;
-#endif
             }
           }
         }
@@ -673,21 +659,8 @@ __global__ void __launch_bounds__((D * 4) * HV, OUTPUT ? ((D == 64 && HV == 1) ?
     }
       }  // MFMA stage
     }
-#ifdef LAWCAT_TIMING
-    const long long tc1 = __builtin_readcyclecounter();
-    if (ls >= 0 && t0 < s1) { if ((ls & 1) == 0) tc_compute += tc1 - tc0; else tc_mfma += tc1 - tc0; }
-#endif
     __syncthreads();
-#ifdef LAWCAT_TIMING
-    tc_barrier += __builtin_readcyclecounter() - tc1;
-#endif
   }
-#ifdef LAWCAT_TIMING
-  if (OUTPUT && a.den_out != nullptr && l == 0) {
-    float* dbg = a.den_out + ((size_t)(blockIdx.y * gridDim.x + blockIdx.x) * (4 * HV) + team * 4 + w) * 4;
-    dbg[0] = (float)tc_compute; dbg[1] = (float)tc_mfma; dbg[2] = (float)(wall0 & 0xffffff); dbg[3] = (float)(wall_clock64() & 0xffffff);
-  }
-#endif
 
   // ---- state out: first pass -> workspace slot (S | z | decay); last segment of the output pass -> S_out, z_out
   float* Sdst = nullptr;
@@ -808,14 +781,14 @@ hipError_t set_lds(K kernel, int bytes) {
 
 extern hipEvent_t g_ev_before, g_ev_after;
 
-template <int D, int GR, int MODE, int HV>
+template <int D, int GR, int MODE>
 hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
   using G = Geo<D, GR>;
   const int heads = a.B * a.Hkv;
   hipError_t e;
   if (a.nseg > 1) {
-    // GR = 0: key side only.  Always one team per workgroup: its compute stage holds a barrier of its own.
-    auto k1 = gla_chunk_kernel<D, 0, MODE, false, 1>;
+    // GR = 0: key side only
+    auto k1 = gla_chunk_kernel<D, 0, MODE, false>;
     constexpr int lds1 = Geo<D, 0>::kBytes;
     static bool set1 = false;
     if (!set1) {
@@ -831,10 +804,10 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  auto k3 = gla_chunk_kernel<D, GR, MODE, true, HV>;
+  auto k3 = gla_chunk_kernel<D, GR, MODE, true>;
   static bool set3 = false;
   if (!set3) {
-    e = set_lds(k3, G::kBytes * HV);
+    e = set_lds(k3, G::kBytes);
     if (e != hipSuccess) return e;
     set3 = true;
   }
@@ -843,20 +816,20 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
     e = hipEventRecord(g_ev_before, stream);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(k3, dim3((a.nseg + HV - 1) / HV, heads), dim3(G::TEAM * HV), G::kBytes * HV, stream, a);
+  hipLaunchKernelGGL(k3, dim3(a.nseg, heads), dim3(G::TEAM), G::kBytes, stream, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (trace) e = hipEventRecord(g_ev_after, stream);
   return e;
 }
 
-template <int D, int HV>
+template <int D>
 hipError_t launch_d(const ChunkArgs& a, int group, int mode, hipStream_t stream) {
 #define LAWCAT_CASE(GRV)                                                       \
   case GRV:                                                                    \
-    if (mode == kPlain) return launch_all<D, GRV, kPlain, HV>(a, stream);      \
-    if (mode == kConvId) return launch_all<D, GRV, kConvId, HV>(a, stream);    \
-    return launch_all<D, GRV, kConvElu, HV>(a, stream);
+    if (mode == kPlain) return launch_all<D, GRV, kPlain>(a, stream);      \
+    if (mode == kConvId) return launch_all<D, GRV, kConvId>(a, stream);    \
+    return launch_all<D, GRV, kConvElu>(a, stream);
   switch (group) {
     LAWCAT_CASE(1)
     LAWCAT_CASE(2)
