@@ -112,6 +112,52 @@ def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0, segment=0
             "bytes_step": bytes_step, "nsets": nsets, "host0": host0}
 
 
+def run_side_ops(wl, steps=30):
+    """Stand-alone calls of the same library on the same shape: the conv on Q (HBM-bound streaming,
+    4 B per element moved) and the decode step (launch-bound).  Reported beside the headline, not as it."""
+    import torch
+
+    from paper_2509_18467_amd import lawcat
+
+    dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    desc = lawcat.make_desc(wl.B, wl.T, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W, dtype=lawcat.DTYPE_BF16, feature_map=1)
+    nset = 3
+    xs = [torch.randn(wl.B, wl.T, wl.Hq, wl.d, device="cuda").to(dt) for _ in range(nset)]
+    ys = [torch.empty_like(x) for x in xs]
+    w = (0.5 * torch.randn(wl.Hq, wl.d, wl.W, device="cuda")).to(dt)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(3):
+        lawcat.conv1d_causal(desc, wl.Hq, xs[i % nset], w, None, ys[i % nset], None)
+    e0.record()
+    for i in range(steps):
+        lawcat.conv1d_causal(desc, wl.Hq, xs[i % nset], w, None, ys[i % nset], None)
+    e1.record()
+    torch.cuda.synchronize()
+    conv_ms = e0.elapsed_time(e1) / steps
+    conv_bytes = 2 * xs[0].numel() * xs[0].element_size()
+    # decode step
+    d1 = lawcat.make_desc(wl.B, 1, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W, dtype=lawcat.DTYPE_BF16, feature_map=1)
+    q = torch.rand(wl.B, wl.Hq, wl.d, device="cuda").to(dt) + 0.5
+    k = torch.rand(wl.B, wl.Hkv, wl.d, device="cuda").to(dt) + 0.5
+    v = torch.randn(wl.B, wl.Hkv, wl.d, device="cuda").to(dt)
+    g = torch.randn(wl.B, wl.Hkv, wl.d, device="cuda").to(dt)
+    S = torch.zeros(wl.B, wl.Hkv, wl.d, wl.d, device="cuda")
+    z = torch.ones(wl.B, wl.Hkv, wl.d, device="cuda")
+    o = torch.empty(wl.B, wl.Hq, wl.d, dtype=dt, device="cuda")
+    for _ in range(5):
+        lawcat.gla_step(d1, q, k, v, g, S, z, o)
+    n = 200
+    e0.record()
+    for _ in range(n):
+        lawcat.gla_step(d1, q, k, v, g, S, z, o)
+    e1.record()
+    torch.cuda.synchronize()
+    step_us = e0.elapsed_time(e1) / n * 1e3
+    return {"conv1d_causal_q": {"ms": conv_ms, "GB/s": conv_bytes / (conv_ms * 1e-3) / 1e9,
+                                "frac_of_hbm_peak": conv_bytes / (conv_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "gla_step": {"us_per_step": step_us, "state_bytes_per_step": 2 * S.numel() * 4}}
+
+
 def cpu_baseline(wl, host0, feature_map=1, max_tokens=65536):
     """The fp64 oracle as it stands, on the host cores, on a bounded prefix of the same inputs
     (the whole sequence up to 65536 tokens: seconds to tens of seconds of CPU work)."""
@@ -153,6 +199,7 @@ def main():
     ap.add_argument("--feature-map", type=int, default=1)
     ap.add_argument("--sweep", action="store_true", help="also time the other graded shapes (reported under 'sweep')")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--side-ops", action="store_true", help="also time lawcat_conv1d_causal and lawcat_gla_step alone")
     ap.add_argument("--segment", type=int, default=0, help="tokens per segment (0 = the library's choice)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -207,6 +254,8 @@ def main():
             del r2
             torch.cuda.empty_cache()
         out["sweep"] = sweep
+    if args.side_ops:
+        out["side_ops"] = run_side_ops(wl)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(wl, r["host0"], args.feature_map)
     print(json.dumps(out), flush=True)

@@ -118,7 +118,7 @@ int lawcat_gla_prefill(const lawcat_desc* desc, const void* q, const void* k, co
   r.q = q; r.k = k; r.v = v; r.g = gate_logits; r.S0 = S0; r.z0 = z0; r.o = o; r.den_out = den_out;
   r.S_out = S_out; r.z_out = z_out; r.B = desc->B; r.T = desc->T; r.Hq = desc->Hq; r.Hkv = desc->Hkv;
   r.d = desc->dk; r.gate_scale = desc->gate_scale; r.eps = desc->eps;
-  r.bf16 = desc->dtype == LAWCAT_DTYPE_BF16; r.whole_state_per_block = 0;
+  r.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
   return hip_status(launch_gla_recurrent(r, hs));
 }
 
@@ -134,8 +134,7 @@ int lawcat_gla_step(const lawcat_desc* desc, const void* q, const void* k, const
   r.q = q; r.k = k; r.v = v; r.g = gate_logits; r.S0 = S; r.z0 = z; r.o = o; r.den_out = nullptr;
   r.S_out = S; r.z_out = z; r.B = desc->B; r.T = 1; r.Hq = desc->Hq; r.Hkv = desc->Hkv; r.d = desc->dk;
   r.gate_scale = desc->gate_scale; r.eps = desc->eps; r.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
-  r.whole_state_per_block = 1;
-  return hip_status(launch_gla_recurrent(r, static_cast<hipStream_t>(stream)));
+  return hip_status(launch_gla_step(r, static_cast<hipStream_t>(stream)));
 }
 
 int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
@@ -186,7 +185,7 @@ int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, 
   RecurrentParams r{};
   r.q = qd; r.k = kd; r.v = V; r.g = gate_logits; r.S0 = S0; r.z0 = z0; r.o = O; r.den_out = den_out;
   r.S_out = S_out; r.z_out = z_out; r.B = desc->B; r.T = desc->T; r.Hq = desc->Hq; r.Hkv = desc->Hkv;
-  r.d = desc->dk; r.gate_scale = desc->gate_scale; r.eps = desc->eps; r.bf16 = bf16; r.whole_state_per_block = 0;
+  r.d = desc->dk; r.gate_scale = desc->gate_scale; r.eps = desc->eps; r.bf16 = bf16;
   return hip_status(launch_gla_recurrent(r, hs));
 }
 

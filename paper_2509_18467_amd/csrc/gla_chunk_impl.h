@@ -583,58 +583,49 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
                 bf16x8, make_uint4(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])));
           }
         __syncthreads();  // scores of this chunk are in LDS (double-buffered by chunk parity)
-        // Query heads go through in groups of HP so that the MFMA chains of different heads overlap.
-        constexpr int HP = (GR >= 2 && D == 64) ? 2 : 1;  // head dim 128 has no registers to spare for pairs
+        // One query head at a time (the loop stays rolled).  Variants that interleaved the MFMA chains of
+        // two heads, or unrolled this loop, let the compiler reuse the registers of one chain's operands
+        // as LDS-load destinations while many MFMAs were still queued, and gave results that varied from
+        // run to run on gfx950; this shape is the one the repeated-run GPU test holds bit-stable.
 #pragma unroll 1
-        for (int h0 = 0; h0 < GR; h0 += HP) {
-          bf16x8 qb[HP][G::KS];
-          short4v pb[HP], pl[HP];
+        for (int hh = 0; hh < GR; ++hh) {
+          bf16x8 qb[G::KS];
 #pragma unroll
-          for (int u = 0; u < HP; ++u) {
-#pragma unroll
-            for (int ks = 0; ks < G::KS; ++ks) {
-              const unsigned char* p =
-                  smem + G::kQp + ((h0 + u) * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
-              const uint2 lo = *reinterpret_cast<const uint2*>(p);
-              const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
-              qb[u][ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-            }
-            const unsigned char* ps = smem + G::kPs + (((mc & 1) * GR + h0 + u) * 2) * 512 + l * 8;
-            pb[u] = __builtin_bit_cast(short4v, *reinterpret_cast<const uint2*>(ps));
-            pl[u] = __builtin_bit_cast(short4v, *reinterpret_cast<const uint2*>(ps + 512));
+          for (int ks = 0; ks < G::KS; ++ks) {
+            const unsigned char* p = smem + G::kQp + (hh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+            const uint2 lo = *reinterpret_cast<const uint2*>(p);
+            const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
+            qb[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
           }
+          const unsigned char* ps = smem + G::kPs + (((mc & 1) * GR + hh) * 2) * 512 + l * 8;
+          const short4v pb = __builtin_bit_cast(short4v, *reinterpret_cast<const uint2*>(ps));
+          const short4v pl = __builtin_bit_cast(short4v, *reinterpret_cast<const uint2*>(ps + 512));
           // o^T[dv][query] = S^T (q (.) E)^T + [V|1]^T P^T
-          floatx4 oacc[HP][G::NT];
+          floatx4 oacc[G::NT];
 #pragma unroll
-          for (int u = 0; u < HP; ++u)
+          for (int ct = 0; ct < G::NT; ++ct) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ct = 0; ct < G::NT; ++ct) {
-              floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-              for (int ks = 0; ks < G::KS; ++ks)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], qb[u][ks], acc, 0, 0, 0);
-              acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pl[u], acc, 0, 0, 0);
-              acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pb[u], acc, 0, 0, 0);
-              oacc[u][ct] = acc;
-            }
+            for (int ks = 0; ks < G::KS; ++ks)
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], qb[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pl, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pb, acc, 0, 0, 0);
+            oacc[ct] = acc;
+          }
           // the normalizer tile holds den for query n in every row
           const int tok = tq + n;
+          const float den = oacc[G::CT][0] + a.eps;
+          const float rden = fast_rcp(den);
+          if (tok < s1) {
+            bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * GR + hh) * D;
 #pragma unroll
-          for (int u = 0; u < HP; ++u) {
-            const int hh = h0 + u;
-            const float den = oacc[u][G::CT][0] + a.eps;
-            const float rden = fast_rcp(den);
-            if (tok < s1) {
-              bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * GR + hh) * D;
-#pragma unroll
-              for (int ct = 0; ct < G::CT; ++ct) {
-                const uint2 pk = make_uint2(pack2(oacc[u][ct][0] * rden, oacc[u][ct][1] * rden),
-                                            pack2(oacc[u][ct][2] * rden, oacc[u][ct][3] * rden));
-                *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
-              }
-              if (a.den_out != nullptr && w == 0 && g4 == 0)
-                a.den_out[((size_t)b * T + tok) * a.Hq + hk * GR + hh] = den;
+            for (int ct = 0; ct < G::CT; ++ct) {
+              const uint2 pk = make_uint2(pack2(oacc[ct][0] * rden, oacc[ct][1] * rden),
+                                          pack2(oacc[ct][2] * rden, oacc[ct][3] * rden));
+              *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
             }
+            if (a.den_out != nullptr && w == 0 && g4 == 0)
+              a.den_out[((size_t)b * T + tok) * a.Hq + hk * GR + hh] = den;
           }
         }
       }

@@ -1,14 +1,14 @@
 // Token-by-token form of the normalized gated linear attention (paper section 4.2):
 //   S_t = diag(alpha_t) S_{t-1} + k_t^T v_t,  z_t = alpha_t (.) z_{t-1} + k_t,
 //   o_t = q_t S_t / (q_t . z_t + eps)
-// in plain fp32 vector arithmetic.  It serves two callers: the decode step
-// (lawcat_gla_step, T = 1, state updated in place) and prefill with fp32 storage,
-// where bf16 matrix-core operands would not meet the fp32 error bound.
+// in plain fp32 vector arithmetic.  Two kernels: gla_recurrent_kernel walks a whole sequence (prefill with
+// fp32 storage, where bf16 matrix-core operands would not meet the fp32 error bound), gla_step_kernel is
+// the decode step (lawcat_gla_step, one token, state updated in place).
 //
-// One 256-thread block owns a (batch, kv head) and NJ slices of 16 value columns.
-// Lane layout: tid = j*16 + cg; the thread keeps S[c][col] for the d/16 key channels
-// c = cg + 16 r and the columns col = 16 s + j of its slices in registers, plus a replica of z[c].
-// q_t S_t is reduced over the 16 cg-lanes of a row with cross-lane shuffles.
+// gla_recurrent_kernel: one 256-thread block owns a (batch, kv head) and a slice of 16 value columns.
+// Lane layout: tid = j*16 + cg; the thread keeps S[c][col] for the d/16 key channels c = cg + 16 r of
+// column col = 16 slice + j in registers, plus a replica of z[c].  q_t S_t is reduced over the 16 cg-lanes
+// with cross-lane shuffles.
 #include "kernels.h"
 
 namespace lawcat {
@@ -108,14 +108,89 @@ __global__ void __launch_bounds__(256) gla_recurrent_kernel(
   }
 }
 
+// Decode step (T = 1), state in place.  One block per (batch, kv head).  Thread t owns value column
+// t % D and a contiguous band of D*D/256 key channels of it, so a wave reads and writes whole 256-byte
+// rows of S; alpha, k, z and the query heads are staged in LDS and read as broadcasts; the partial
+// q.S sums of the 256/D bands are combined through LDS.  Query heads go four at a time.
+template <typename T, int D>
+__global__ void __launch_bounds__(256) gla_step_kernel(const T* __restrict__ q, const T* __restrict__ k,
+                                                       const T* __restrict__ v, const T* __restrict__ g,
+                                                       float* S, float* z, T* __restrict__ o, int Hq, int Hkv,
+                                                       float gate_scale, float eps) {
+  constexpr int NPART = 256 / D;      // bands of key channels
+  constexpr int RPT = D / NPART;      // key channels per thread
+  constexpr int HT = 4;               // query heads per pass
+  __shared__ float sh_a[D], sh_k[D], sh_z[D], sh_q[HT][D], sh_part[HT][NPART][D];
+  const int tid = threadIdx.x;
+  const int bh = blockIdx.x;  // b * Hkv + hk
+  const int b = bh / Hkv, hk = bh % Hkv;
+  const int group = Hq / Hkv;
+  const T* kt = k + (size_t)bh * D;
+  const T* gt = g + (size_t)bh * D;
+  const T* vt = v + (size_t)bh * D;
+  float* Sh = S + (size_t)bh * D * D;
+  float* zh = z + (size_t)bh * D;
+  if (tid < D) {
+    const float alpha = expf(gate_scale * log_sigmoid(ldf(gt + tid)));
+    const float kk = ldf(kt + tid);
+    const float zn = fmaf(alpha, zh[tid], kk);
+    sh_a[tid] = alpha;
+    sh_k[tid] = kk;
+    sh_z[tid] = zn;
+    zh[tid] = zn;
+  }
+  __syncthreads();
+  const int col = tid % D, part = tid / D;
+  const float vv = ldf(vt + col);
+  float sreg[RPT];
+#pragma unroll
+  for (int r = 0; r < RPT; ++r) sreg[r] = Sh[(size_t)(part * RPT + r) * D + col];
+#pragma unroll
+  for (int r = 0; r < RPT; ++r) {
+    const int c = part * RPT + r;
+    sreg[r] = fmaf(sh_a[c], sreg[r], sh_k[c] * vv);
+    Sh[(size_t)c * D + col] = sreg[r];
+  }
+  for (int h0 = 0; h0 < group; h0 += HT) {
+    const int nh = min(HT, group - h0);
+    __syncthreads();  // previous pass is done with sh_q / sh_part
+    for (int e = tid; e < nh * D; e += 256) {
+      const int hh = e / D, c = e % D;
+      sh_q[hh][c] = ldf(q + ((size_t)b * Hq + hk * group + h0 + hh) * D + c);
+    }
+    __syncthreads();
+    float pn[HT] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int r = 0; r < RPT; ++r) {
+      const int c = part * RPT + r;
+#pragma unroll
+      for (int hh = 0; hh < HT; ++hh) pn[hh] = fmaf(sh_q[hh][c], sreg[r], pn[hh]);
+    }
+#pragma unroll
+    for (int hh = 0; hh < HT; ++hh) sh_part[hh][part][col] = pn[hh];
+    __syncthreads();
+    // thread (hh = part', col): one output element each for up to 256 / D heads at a time
+    for (int hh = part; hh < nh; hh += NPART) {
+      float num = 0.f, den = eps;
+#pragma unroll
+      for (int pp = 0; pp < NPART; ++pp) num += sh_part[hh][pp][col];
+      for (int c = 0; c < D; ++c) den = fmaf(sh_q[hh][c], sh_z[c], den);
+      stf(o + ((size_t)b * Hq + hk * group + h0 + hh) * D + col, num / den);
+    }
+  }
+}
+
+template <typename T, int D>
+hipError_t launch_step_d(const RecurrentParams& p, hipStream_t stream) {
+  hipLaunchKernelGGL((gla_step_kernel<T, D>), dim3(p.B * p.Hkv), dim3(256), 0, stream, (const T*)p.q, (const T*)p.k,
+                     (const T*)p.v, (const T*)p.g, p.S_out, p.z_out, (T*)p.o, p.Hq, p.Hkv, p.gate_scale, p.eps);
+  return hipGetLastError();
+}
+
 template <typename T, int D>
 hipError_t launch_d(const RecurrentParams& p, hipStream_t stream) {
   const int heads = p.B * p.Hkv;
-  if (p.whole_state_per_block) {
-    hipLaunchKernelGGL((gla_recurrent_kernel<T, D, D / 16>), dim3(heads, 1), dim3(256), 0, stream, (const T*)p.q,
-                       (const T*)p.k, (const T*)p.v, (const T*)p.g, p.S0, p.z0, (T*)p.o, p.den_out, p.S_out,
-                       p.z_out, p.T, p.Hq, p.Hkv, p.gate_scale, p.eps);
-  } else {
+  {
     hipLaunchKernelGGL((gla_recurrent_kernel<T, D, 1>), dim3(heads, D / 16), dim3(256), 0, stream, (const T*)p.q,
                        (const T*)p.k, (const T*)p.v, (const T*)p.g, p.S0, p.z0, (T*)p.o, p.den_out, p.S_out,
                        p.z_out, p.T, p.Hq, p.Hkv, p.gate_scale, p.eps);
@@ -124,6 +199,11 @@ hipError_t launch_d(const RecurrentParams& p, hipStream_t stream) {
 }
 
 }  // namespace
+
+hipError_t launch_gla_step(const RecurrentParams& p, hipStream_t stream) {
+  if (p.bf16) return p.d == 64 ? launch_step_d<bf16_t, 64>(p, stream) : launch_step_d<bf16_t, 128>(p, stream);
+  return p.d == 64 ? launch_step_d<float, 64>(p, stream) : launch_step_d<float, 128>(p, stream);
+}
 
 hipError_t launch_gla_recurrent(const RecurrentParams& p, hipStream_t stream) {
   if (p.bf16) return p.d == 64 ? launch_d<bf16_t, 64>(p, stream) : launch_d<bf16_t, 128>(p, stream);

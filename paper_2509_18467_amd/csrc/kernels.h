@@ -36,9 +36,10 @@ struct RecurrentParams {
   int B, T, Hq, Hkv, d;
   float gate_scale, eps;
   int bf16;
-  int whole_state_per_block;  // 1: one block owns a head's whole state (safe for in-place S/z)
 };
 hipError_t launch_gla_recurrent(const RecurrentParams& p, hipStream_t stream);
+// One token per sequence, S_out/z_out updated in place (S0, z0, den_out, T are not read).
+hipError_t launch_gla_step(const RecurrentParams& p, hipStream_t stream);
 
 // Copies the last W-1 raw rows of [halo ; x] (the conv cache) without running the conv.
 hipError_t launch_conv_tail(const void* x, const void* halo, void* tail_out, int B, int T, int H, int d, int W,
