@@ -101,36 +101,35 @@ struct Raw {
   uint32_t q[NQ][11];
 };
 
-// Uniform (per workgroup) row addressing of one input tensor.
+// Uniform (per workgroup) row addressing of one input tensor: a raw buffer descriptor over the rows of this
+// batch element, starting at this head's columns.  A load whose byte offset falls outside [0, bytes) returns
+// zero, which supplies the zero rows before the first token (their offsets wrap around to huge values) and
+// past the last one without a branch.
 struct RowSrc {
-  const char* base;   // first row of this batch, at this head's columns
+  __amdgpu_buffer_rsrc_t rsrc;
   const char* halo;   // nullable: first halo row of this batch, at this head's columns
   unsigned stride;    // bytes per token row
 };
 
-// Interior granule: every row t0-3 .. t0+NTG-1 exists.  Scalar row base + one per-thread offset.
-template <bool CONV>
-__device__ inline void load_rows_interior(const RowSrc& s, int t0, unsigned voff, uint32_t (&raw)[11]) {
-  const char* gb = s.base + (size_t)(t0 - 3) * s.stride;
-#pragma unroll
-  for (int j = CONV ? 0 : 3; j < 11; ++j)
-    raw[j] = *reinterpret_cast<const uint32_t*>(gb + (size_t)j * s.stride + voff);
+__device__ inline RowSrc make_row_src(const char* base, const char* halo, unsigned stride, int T, unsigned width) {
+  // stride field 0 (raw buffer); 0x00020000 = 32-bit data format of gfx9-family descriptors.  The host has
+  // checked that (T + 4) * stride fits 32 bits.
+  const unsigned bytes = (unsigned)(T - 1) * stride + width;
+  return RowSrc{__builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000), halo, stride};
 }
 
-// Edge granule (start of the sequence or ragged end): rows before the sequence come from the halo
-// or are zero, rows at or past `tend` are zero.
+// Rows t0-3 .. t0+7 (+ this thread's patch offset, folded into voff) of one tensor.  t0 is uniform.
 template <bool CONV>
-__device__ inline void load_rows_edge(const RowSrc& s, int tok0, int tend, int W, unsigned coff, uint32_t (&raw)[11]) {
+__device__ inline void load_rows(const RowSrc& s, int t0, int tl0, int W, unsigned voff, unsigned coff,
+                                 uint32_t (&raw)[11]) {
 #pragma unroll
-  for (int j = CONV ? 0 : 3; j < 11; ++j) {
-    const int tok = tok0 - 3 + j;
-    uint32_t r = 0u;
-    if (tok >= 0) {
-      if (tok < tend) r = *reinterpret_cast<const uint32_t*>(s.base + (size_t)tok * s.stride + coff);
-    } else if (CONV && s.halo != nullptr && tok >= -(W - 1)) {
-      r = *reinterpret_cast<const uint32_t*>(s.halo + (size_t)(W - 1 + tok) * s.stride + coff);
-    }
-    raw[j] = r;
+  for (int j = CONV ? 0 : 3; j < 11; ++j)
+    raw[j] = __builtin_amdgcn_raw_buffer_load_b32(s.rsrc, (int)(voff + (unsigned)(t0 - 3 + j) * s.stride), 0, 0);
+  if (CONV && t0 == 0 && s.halo != nullptr && tl0 == 0) {
+    // the rows before the first token come from the caller's halo (oldest row first, W-1 rows)
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+      if (j - 3 >= -(W - 1)) raw[j] = *reinterpret_cast<const uint32_t*>(s.halo + (size_t)(W - 4 + j) * s.stride + coff);
   }
 }
 
@@ -179,37 +178,21 @@ struct Kernel {
   __device__ static inline void fetch(Raw<NQ>& raw, const RowSrc& srcK, const RowSrc& srcG, const RowSrc& srcV,
                                       const RowSrc& srcQ, int t0, int s1, int tl0, unsigned coff, int W) {
     constexpr int H0 = PART == 0 ? 0 : NQE, H1 = PART == 0 ? NQE : (OUTPUT ? NQ : 0);
-    const bool edge = (t0 < 3) || (t0 + G::NTG > s1);
-    if (!edge) {
-      if (PART == 0) {
-        const unsigned voffkv = (unsigned)tl0 * srcK.stride + coff;
-        load_rows_interior<false>(srcG, t0, voffkv, raw.g);
-        load_rows_interior<CONV>(srcK, t0, voffkv, raw.k);
-        load_rows_interior<false>(srcV, t0, voffkv, raw.v);
-      }
-      const unsigned voffq = (unsigned)tl0 * srcQ.stride + coff;
-#pragma unroll
-      for (int hh = H0; hh < H1; ++hh) load_rows_interior<CONV>(srcQ, t0, voffq + hh * D * 2, raw.q[hh]);
-    } else {
-      const int tok0 = t0 + tl0;
-      if (PART == 0) {
-        load_rows_edge<false>(srcG, tok0, s1, 1, coff, raw.g);
-        load_rows_edge<CONV>(srcK, tok0, s1, W, coff, raw.k);
-        load_rows_edge<false>(srcV, tok0, s1, 1, coff, raw.v);
-      }
-#pragma unroll
-      for (int hh = H0; hh < H1; ++hh) load_rows_edge<CONV>(srcQ, tok0, s1, W, coff + hh * D * 2, raw.q[hh]);
+    if (PART == 0) {
+      const unsigned voffkv = (unsigned)tl0 * srcK.stride + coff;
+      load_rows<false>(srcG, t0, tl0, 1, voffkv, coff, raw.g);
+      load_rows<CONV>(srcK, t0, tl0, W, voffkv, coff, raw.k);
+      load_rows<false>(srcV, t0, tl0, 1, voffkv, coff, raw.v);
     }
+    const unsigned voffq = (unsigned)tl0 * srcQ.stride + coff;
+#pragma unroll
+    for (int hh = H0; hh < H1; ++hh) load_rows<CONV>(srcQ, t0, tl0, W, voffq + hh * D * 2, coff + hh * D * 2, raw.q[hh]);
   }
 
   // One late query head (index >= NQE) of the granule at t0.
   __device__ static inline void fetch_head(Raw<NQ>& raw, const RowSrc& srcQ, int hh, int t0, int s1, int tl0,
                                            unsigned coff, int W) {
-    const bool edge = (t0 < 3) || (t0 + G::NTG > s1);
-    if (!edge)
-      load_rows_interior<CONV>(srcQ, t0, (unsigned)tl0 * srcQ.stride + coff + hh * D * 2, raw.q[hh]);
-    else
-      load_rows_edge<CONV>(srcQ, t0 + tl0, s1, W, coff + hh * D * 2, raw.q[hh]);
+    load_rows<CONV>(srcQ, t0, tl0, W, (unsigned)tl0 * srcQ.stride + coff + hh * D * 2, coff + hh * D * 2, raw.q[hh]);
   }
 
   // ---- registers -> LDS operands: gate products, conv + phi, scaling by the decay, bf16 packing
@@ -442,14 +425,15 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
 
   // uniform row sources
   const unsigned kvstride = (unsigned)a.Hkv * D * 2, qstride = (unsigned)a.Hq * D * 2;
-  const RowSrc srcK{(const char*)a.k + ((size_t)b * T * a.Hkv + hk) * D * 2,
-                    (CONV && a.k_halo) ? (const char*)a.k_halo + ((size_t)b * (a.W - 1) * a.Hkv + hk) * D * 2 : nullptr,
-                    kvstride};
-  const RowSrc srcG{(const char*)a.g + ((size_t)b * T * a.Hkv + hk) * D * 2, nullptr, kvstride};
-  const RowSrc srcV{(const char*)a.v + ((size_t)b * T * a.Hkv + hk) * D * 2, nullptr, kvstride};
-  const RowSrc srcQ{(const char*)a.q + ((size_t)b * T * a.Hq + hk * GR) * D * 2,
-                    (CONV && a.q_halo) ? (const char*)a.q_halo + ((size_t)b * (a.W - 1) * a.Hq + hk * GR) * D * 2 : nullptr,
-                    qstride};
+  const RowSrc srcK = make_row_src(
+      (const char*)a.k + ((size_t)b * T * a.Hkv + hk) * D * 2,
+      (CONV && a.k_halo) ? (const char*)a.k_halo + ((size_t)b * (a.W - 1) * a.Hkv + hk) * D * 2 : nullptr, kvstride, T, D * 2);
+  const RowSrc srcG = make_row_src((const char*)a.g + ((size_t)b * T * a.Hkv + hk) * D * 2, nullptr, kvstride, T, D * 2);
+  const RowSrc srcV = make_row_src((const char*)a.v + ((size_t)b * T * a.Hkv + hk) * D * 2, nullptr, kvstride, T, D * 2);
+  const RowSrc srcQ = make_row_src(
+      (const char*)a.q + ((size_t)b * T * a.Hq + hk * GR) * D * 2,
+      (CONV && a.q_halo) ? (const char*)a.q_halo + ((size_t)b * (a.W - 1) * a.Hq + hk * GR) * D * 2 : nullptr, qstride, T,
+      (GR > 0 ? GR : 1) * D * 2);
   const unsigned coff = (unsigned)c0 * 2;
 
   // ---- state in accumulators: Sacc[rt][ct][i] = S[16 rt + 4 g4 + i][16 tile(ct) + n]; ct == CT holds z replicated
