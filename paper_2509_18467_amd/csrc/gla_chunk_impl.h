@@ -75,7 +75,7 @@ struct Geo {
   static constexpr int kVt = kKd + D * TRS;
   static constexpr int kEb = kVt + D * TRS;
   static constexpr int kWl = kEb + MCG * D * 4;
-  static constexpr int kPs = kWl + (GR + 1) * D * 16;   // shared scores: [2 buffers][GR heads][hi, lo][64 lanes] x 8 B
+  static constexpr int kPs = kWl + (GR + 1) * D * 16;   // shared scores: [2 buffers][GR heads][64 lanes] x 16 B (4 high parts, 4 residuals)
   static constexpr int kBytes = kPs + 2 * GR * 2 * 512;
   static constexpr int kSlot = D * D + 2 * D;  // floats per workspace slot: S | z | decay
 };
@@ -155,8 +155,9 @@ __device__ inline void conv_phi(const uint32_t (&raw)[11], const float* wts /*[2
     float a1 = w1[0] * x1[i + 3];
     a1 = fmaf(w1[1], x1[i + 2], a1); a1 = fmaf(w1[2], x1[i + 1], a1); a1 = fmaf(w1[3], x1[i], a1);
     if (MODE == kConvElu) {
-      a0 = fmaf(fmaxf(a0, 0.f), kLn2, fminf(fast_exp2(a0), 1.f));
-      a1 = fmaf(fmaxf(a1, 0.f), kLn2, fminf(fast_exp2(a1), 1.f));
+      // med3(x, 0, 1) of a non-negative x is min(x, 1); written this way it folds into the clamp bit of v_exp_f32
+      a0 = fmaf(fmaxf(a0, 0.f), kLn2, __builtin_amdgcn_fmed3f(fast_exp2(a0), 0.f, 1.f));
+      a1 = fmaf(fmaxf(a1, 0.f), kLn2, __builtin_amdgcn_fmed3f(fast_exp2(a1), 0.f, 1.f));
     }
     y[i][0] = a0;
     y[i][1] = a1;
@@ -203,7 +204,10 @@ struct Kernel {
     const int tok0 = t0 + tl0;
     // late query heads are fetched one head ahead of their use
     if (OUTPUT && NQE < NQ) fetch_head(raw, srcQ, NQE, t0, s1, tl0, coff, W);
-    float E[8][2], IE[8][2];
+    // keys first: conv + phi into kf, which the gate loop below scales in place by 1/E as it goes
+    float kf[8][2];
+    conv_phi<MODE>(raw.k, wl + ((size_t)GR * D + c0) * 4, kf);
+    float E[8][2];
     float run[2] = {1.f, 1.f}, irun[2] = {1.f, 1.f};
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -224,7 +228,7 @@ struct Kernel {
         run[ch] *= al;
         irun[ch] *= ia;
         E[i][ch] = run[ch];
-        IE[i][ch] = irun[ch];
+        kf[i][ch] = (EDGE && tok0 + i >= s1) ? 0.f : kf[i][ch] * irun[ch];
       }
     }
     // the other half of the chunk lives 32 lanes away
@@ -239,8 +243,6 @@ struct Kernel {
     }
     __builtin_amdgcn_sched_barrier(0);  // keep the sections apart: bounds live registers
     // keys: K' = k/E (in-chunk scores) and Kdec = k E_last/E (state update)
-    float kf[8][2];
-    conv_phi<MODE>(raw.k, wl + ((size_t)GR * D + c0) * 4, kf);
     unsigned char* kp = smem + G::kKp + tl0 * G::QRS + c0 * 2;
     float kdv[8][2];
 #pragma unroll
@@ -248,8 +250,7 @@ struct Kernel {
 #pragma unroll
       for (int ch = 0; ch < 2; ++ch) {
         E[i][ch] *= pre[ch];
-        const float kk = (EDGE && tok0 + i >= s1) ? 0.f : kf[i][ch];
-        const float kprime = kk * (IE[i][ch] * ipre[ch]);
+        const float kprime = kf[i][ch] * ipre[ch];
         kf[i][ch] = kprime;
         kdv[i][ch] = kprime * btot[ch];
       }
@@ -551,9 +552,8 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
           const uint2 lo2 = make_uint2(pack2(pt[0] - bf_lo(ph0), pt[1] - bf_hi(ph0)),
                                        pack2(pt[2] - bf_lo(ph1), pt[3] - bf_hi(ph1)));
           if (w < GR) {
-            unsigned char* ps = smem + G::kPs + (((mc & 1) * GR + myh) * 2) * 512 + l * 8;
-            *reinterpret_cast<uint2*>(ps) = hi2;
-            *reinterpret_cast<uint2*>(ps + 512) = lo2;
+            unsigned char* ps = smem + G::kPs + ((mc & 1) * GR + myh) * 1024 + l * 16;
+            *reinterpret_cast<uint4*>(ps) = make_uint4(hi2.x, hi2.y, lo2.x, lo2.y);
           }
         }
         // state as bf16 A-fragments: rows = value columns, k = key channels {4 g4 + i, 16 + 4 g4 + i} of each 32
@@ -566,6 +566,13 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
             sa[ct][ks] = __builtin_bit_cast(
                 bf16x8, make_uint4(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])));
           }
+        // [V|1]^T against (high, residual) in one k = 32 MFMA: the same four tokens fill both halves of A
+        bf16x8 vv[G::NT];
+#pragma unroll
+        for (int ct = 0; ct < G::NT; ++ct) {
+          const uint2 r = __builtin_bit_cast(uint2, vfrag[ct]);
+          vv[ct] = __builtin_bit_cast(bf16x8, make_uint4(r.x, r.y, r.x, r.y));
+        }
         __syncthreads();  // scores of this chunk are in LDS (double-buffered by chunk parity)
         // One query head at a time (the loop stays rolled).  Variants that interleaved the MFMA chains of
         // two heads, or unrolled this loop, let the compiler reuse the registers of one chain's operands
@@ -581,9 +588,9 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
             const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
             qb[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
           }
-          const unsigned char* ps = smem + G::kPs + (((mc & 1) * GR + hh) * 2) * 512 + l * 8;
-          const short4v pb = __builtin_bit_cast(short4v, *reinterpret_cast<const uint2*>(ps));
-          const short4v pl = __builtin_bit_cast(short4v, *reinterpret_cast<const uint2*>(ps + 512));
+          // scores as one k = 32 operand: slots 0..3 the high parts, 4..7 the residuals of this lane's 4 keys
+          const unsigned char* ps = smem + G::kPs + ((mc & 1) * GR + hh) * 1024 + l * 16;
+          const bf16x8 pp = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ps));
           // o^T[dv][query] = S^T (q (.) E)^T + [V|1]^T P^T
           floatx4 oacc[G::NT];
 #pragma unroll
@@ -592,8 +599,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
 #pragma unroll
             for (int ks = 0; ks < G::KS; ++ks)
               acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], qb[ks], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pl, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vfrag[ct], pb, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[ct], pp, acc, 0, 0, 0);
             oacc[ct] = acc;
           }
           // the normalizer tile holds den for query n in every row
