@@ -76,7 +76,8 @@ struct Geo {
   static constexpr int kEb = kVt + D * TRS;
   static constexpr int kWl = kEb + MCG * D * 4;
   static constexpr int kPs = kWl + (GR + 1) * D * 16;   // shared scores: [2 buffers][GR heads][64 lanes] x 16 B (4 high parts, 4 residuals)
-  static constexpr int kBytes = kPs + 2 * GR * 2 * 512;
+  static constexpr int kDn = kPs + 2 * GR * 2 * 512;      // shared denominators: [2 buffers][GR heads][16 queries] fp32
+  static constexpr int kBytes = kDn + 2 * GR * 64;
   static constexpr int kSlot = D * D + 2 * D;  // floats per workspace slot: S | z | decay
 };
 
@@ -528,35 +529,8 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
       vfrag[G::CT] = short4v{0x3F80, 0x3F80, 0x3F80, 0x3F80};  // ones: the normalizer columns
 
       if (OUTPUT) {
-        // ---- scores: wave w computes P^T = K' Q'^T for query head w % GR only and shares it through LDS
-        const int myh = w % GR;
-        {
-          floatx4 pt = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int ks = 0; ks < G::KS; ++ks) {
-            const unsigned char* pk = smem + G::kKp + (kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
-            const unsigned char* pq = smem + G::kQp + (myh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
-            const uint2 klo = *reinterpret_cast<const uint2*>(pk), khi = *reinterpret_cast<const uint2*>(pk + 32);
-            const uint2 qlo = *reinterpret_cast<const uint2*>(pq), qhi = *reinterpret_cast<const uint2*>(pq + 32);
-            pt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8, make_uint4(klo.x, klo.y, khi.x, khi.y)),
-                __builtin_bit_cast(bf16x8, make_uint4(qlo.x, qlo.y, qhi.x, qhi.y)), pt, 0, 0, 0);
-          }
-          // P^T[key 4 g4 + i][query n], causal: key <= query
-#pragma unroll
-          for (int i = 0; i < 4; ++i) pt[i] = (4 * g4 + i <= n) ? pt[i] : 0.f;
-          // The weights of the few nearest keys dominate the output, so their bf16 rounding would not
-          // average out: carry P as a bf16 pair (high part + residual), two small MFMAs instead of one.
-          const uint32_t ph0 = pack2(pt[0], pt[1]), ph1 = pack2(pt[2], pt[3]);
-          const uint2 hi2 = make_uint2(ph0, ph1);
-          const uint2 lo2 = make_uint2(pack2(pt[0] - bf_lo(ph0), pt[1] - bf_hi(ph0)),
-                                       pack2(pt[2] - bf_lo(ph1), pt[3] - bf_hi(ph1)));
-          if (w < GR) {
-            unsigned char* ps = smem + G::kPs + ((mc & 1) * GR + myh) * 1024 + l * 16;
-            *reinterpret_cast<uint4*>(ps) = make_uint4(hi2.x, hi2.y, lo2.x, lo2.y);
-          }
-        }
-        // state as bf16 A-fragments: rows = value columns, k = key channels {4 g4 + i, 16 + 4 g4 + i} of each 32
+        // state as bf16 A-fragments: rows = value columns, k = key channels {4 g4 + i, 16 + 4 g4 + i} of each 32;
+        // tile CT is the normalizer z, the same in every row
         bf16x8 sa[G::NT][G::KS];
 #pragma unroll
         for (int ct = 0; ct < G::NT; ++ct)
@@ -566,14 +540,48 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
             sa[ct][ks] = __builtin_bit_cast(
                 bf16x8, make_uint4(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])));
           }
-        // [V|1]^T against (high, residual) in one k = 32 MFMA: the same four tokens fill both halves of A
-        bf16x8 vv[G::NT];
+        // ---- scores and denominators: wave w < GR computes, for query head w alone, P^T = K' Q'^T and
+        // den = q' . z + (column sums of the masked P), and shares both through LDS.  Computing the denominator
+        // once per head instead of once per wave saves every wave a whole accumulator tile per head.
+        if (w < GR) {
+          const int myh = w;
+          floatx4 pt = {0.f, 0.f, 0.f, 0.f}, dz = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ct = 0; ct < G::NT; ++ct) {
+          for (int ks = 0; ks < G::KS; ++ks) {
+            const unsigned char* pk = smem + G::kKp + (kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+            const unsigned char* pq = smem + G::kQp + (myh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+            const uint2 klo = *reinterpret_cast<const uint2*>(pk), khi = *reinterpret_cast<const uint2*>(pk + 32);
+            const uint2 qlo = *reinterpret_cast<const uint2*>(pq), qhi = *reinterpret_cast<const uint2*>(pq + 32);
+            const bf16x8 qf = __builtin_bit_cast(bf16x8, make_uint4(qlo.x, qlo.y, qhi.x, qhi.y));
+            pt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, make_uint4(klo.x, klo.y, khi.x, khi.y)), qf, pt, 0, 0, 0);
+            dz = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[G::CT][ks], qf, dz, 0, 0, 0);
+          }
+          // P^T[key 4 g4 + i][query n], causal: key <= query
+#pragma unroll
+          for (int i = 0; i < 4; ++i) pt[i] = (4 * g4 + i <= n) ? pt[i] : 0.f;
+          // The weights of the few nearest keys dominate the output, so their bf16 rounding would not
+          // average out: carry P as a bf16 pair (high part + residual) in one k = 32 operand.
+          const uint32_t ph0 = pack2(pt[0], pt[1]), ph1 = pack2(pt[2], pt[3]);
+          const uint32_t pl0 = pack2(pt[0] - bf_lo(ph0), pt[1] - bf_hi(ph0));
+          const uint32_t pl1 = pack2(pt[2] - bf_lo(ph1), pt[3] - bf_hi(ph1));
+          unsigned char* ps = smem + G::kPs + ((mc & 1) * GR + myh) * 1024 + l * 16;
+          *reinterpret_cast<uint4*>(ps) = make_uint4(ph0, ph1, pl0, pl1);
+          // column sum over the 16 keys: 4 in this lane, the other 12 in the lanes 16, 32 and 48 away
+          float cs = (pt[0] + pt[1]) + (pt[2] + pt[3]);
+          cs += __shfl_xor(cs, 16);
+          cs += __shfl_xor(cs, 32);
+          if (g4 == 0)
+            *reinterpret_cast<float*>(smem + G::kDn + (((mc & 1) * GR + myh) * 16 + n) * 4) = dz[0] + cs + a.eps;
+        }
+        // [V|1]^T against (high, residual) in one k = 32 MFMA: the same four tokens fill both halves of A
+        bf16x8 vv[G::CT];
+#pragma unroll
+        for (int ct = 0; ct < G::CT; ++ct) {
           const uint2 r = __builtin_bit_cast(uint2, vfrag[ct]);
           vv[ct] = __builtin_bit_cast(bf16x8, make_uint4(r.x, r.y, r.x, r.y));
         }
-        __syncthreads();  // scores of this chunk are in LDS (double-buffered by chunk parity)
+        __syncthreads();  // scores and denominators of this chunk are in LDS (double-buffered by chunk parity)
         // One query head at a time (the loop stays rolled).  Variants that interleaved the MFMA chains of
         // two heads, or unrolled this loop, let the compiler reuse the registers of one chain's operands
         // as LDS-load destinations while many MFMAs were still queued, and gave results that varied from
@@ -592,9 +600,9 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
           const unsigned char* ps = smem + G::kPs + ((mc & 1) * GR + hh) * 1024 + l * 16;
           const bf16x8 pp = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ps));
           // o^T[dv][query] = S^T (q (.) E)^T + [V|1]^T P^T
-          floatx4 oacc[G::NT];
+          floatx4 oacc[G::CT];
 #pragma unroll
-          for (int ct = 0; ct < G::NT; ++ct) {
+          for (int ct = 0; ct < G::CT; ++ct) {
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < G::KS; ++ks)
@@ -602,9 +610,8 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[ct], pp, acc, 0, 0, 0);
             oacc[ct] = acc;
           }
-          // the normalizer tile holds den for query n in every row
           const int tok = tq + n;
-          const float den = oacc[G::CT][0] + a.eps;
+          const float den = *reinterpret_cast<const float*>(smem + G::kDn + (((mc & 1) * GR + hh) * 16 + n) * 4);
           const float rden = fast_rcp(den);
           if (tok < s1) {
             bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * GR + hh) * D;
