@@ -481,15 +481,12 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
   if (s0 < s1) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, tfirst, s1, tl0, coff, a.W);
   __syncthreads();  // conv weights are in LDS
 
-  // Stage sequence: compute(0) mfma(0) compute(1) mfma(1) ..., a barrier after each.
-  const int ngran = a.seg_len / G::NTG;
-  const int nstage = 2 * ngran;
+  // Per granule: compute stage, barrier, MFMA stage, barrier.
 #pragma unroll 1
-  for (int st = 0; st < nstage; ++st) {
-    const int ls = st;
-    const int t0 = tfirst + (ls >> 1) * tstep;
-    if (ls >= 0 && (ls >> 1) < nseg_gran) {
-      if ((ls & 1) == 0) {
+  for (int gi = 0; gi < nseg_gran; ++gi) {
+    const int t0 = tfirst + gi * tstep;
+    {
+      {
         // =========================== compute stage: registers -> LDS operands ===========================
         const bool edge = (t0 < 3) || (t0 + G::NTG > s1);
         if (!OUTPUT) {
@@ -509,9 +506,11 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
           KK::template compute<true, true>(raw, srcQ, coff, a.W, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
         else
           KK::template compute<true, false>(raw, srcQ, coff, a.W, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
-      } else {
+      }
+      __syncthreads();
+      {
         // next granule's rows travel while the matrix cores work
-        if ((ls >> 1) + 1 < nseg_gran) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, t0 + tstep, s1, tl0, coff, a.W);
+        if (gi + 1 < nseg_gran) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, t0 + tstep, s1, tl0, coff, a.W);
 
     // =========================== MFMA stage: 16 tokens at a time ===========================
 #pragma unroll 1
