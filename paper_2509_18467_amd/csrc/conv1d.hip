@@ -9,11 +9,16 @@
 namespace lawcat {
 namespace {
 
-constexpr int kStrip = 16;  // tokens per thread
+constexpr int kStrip = 32;  // tokens per thread
+constexpr int kGroup = 4;   // rows fetched together, one group ahead of the arithmetic
 
 template <typename T> struct Io;
 template <> struct Io<float> {
   static constexpr int VEC = 4;
+  typedef float4 Raw;
+  __device__ static Raw load_raw(const float* p) { return *reinterpret_cast<const float4*>(p); }
+  __device__ static Raw zero_raw() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+  __device__ static void unpack(const Raw& r, float (&f)[VEC]) { f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w; }
   __device__ static void load(const float* p, float (&f)[VEC]) {
     float4 r = *reinterpret_cast<const float4*>(p);
     f[0] = r.x; f[1] = r.y; f[2] = r.z; f[3] = r.w;
@@ -25,6 +30,17 @@ template <> struct Io<float> {
 };
 template <> struct Io<bf16_t> {
   static constexpr int VEC = 8;
+  typedef uint4 Raw;
+  __device__ static Raw load_raw(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  __device__ static Raw zero_raw() { return make_uint4(0u, 0u, 0u, 0u); }
+  __device__ static void unpack(const Raw& r, float (&f)[VEC]) {
+    const uint32_t u[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(u[i] << 16);
+      f[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+    }
+  }
   __device__ static void load(const bf16_t* p, float (&f)[VEC]) {
     uint4 r = *reinterpret_cast<const uint4*>(p);
     uint32_t u[4] = {r.x, r.y, r.z, r.w};
@@ -90,22 +106,43 @@ __global__ void __launch_bounds__(256) conv1d_causal_kernel(const T* __restrict_
       for (int i = 0; i < VEC; ++i) win[j][i] = 0.f;
     }
   }
-  const int t1 = min(Tn, t0 + kStrip);
-  for (int t = t0; t < t1; ++t) {
-    float cur[VEC], out[VEC];
-    Io<T>::load(x + ((size_t)b * Tn + t) * rowlen + e0, cur);
+  // Rows travel in groups of kGroup, the next group's loads issued before this group's arithmetic, so that
+  // every thread keeps kGroup 16-byte loads in flight.
+  typedef typename Io<T>::Raw Raw;
+  const T* xb = x + ((size_t)b * Tn) * rowlen + e0;
+  T* yb = y + ((size_t)b * Tn) * rowlen + e0;
+  Raw nxt[kGroup];
 #pragma unroll
-    for (int i = 0; i < VEC; ++i) {
-      float acc = wt[0][i] * cur[i];
-      acc = fmaf(wt[1][i], win[0][i], acc);
-      acc = fmaf(wt[2][i], win[1][i], acc);
-      acc = fmaf(wt[3][i], win[2][i], acc);
-      out[i] = apply_phi(acc, phi);
-      win[2][i] = win[1][i];
-      win[1][i] = win[0][i];
-      win[0][i] = cur[i];
+  for (int r = 0; r < kGroup; ++r) nxt[r] = (t0 + r < Tn) ? Io<T>::load_raw(xb + (size_t)(t0 + r) * rowlen) : Io<T>::zero_raw();
+#pragma unroll 1
+  for (int tg = t0; tg < t0 + kStrip && tg < Tn; tg += kGroup) {
+    Raw cur[kGroup];
+#pragma unroll
+    for (int r = 0; r < kGroup; ++r) cur[r] = nxt[r];
+    if (tg + kGroup < t0 + kStrip) {
+#pragma unroll
+      for (int r = 0; r < kGroup; ++r) {
+        const int t = tg + kGroup + r;
+        nxt[r] = (t < Tn) ? Io<T>::load_raw(xb + (size_t)t * rowlen) : Io<T>::zero_raw();
+      }
     }
-    Io<T>::store(y + ((size_t)b * Tn + t) * rowlen + e0, out);
+#pragma unroll
+    for (int r = 0; r < kGroup; ++r) {
+      float c[VEC], out[VEC];
+      Io<T>::unpack(cur[r], c);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) {
+        float acc = wt[0][i] * c[i];
+        acc = fmaf(wt[1][i], win[0][i], acc);
+        acc = fmaf(wt[2][i], win[1][i], acc);
+        acc = fmaf(wt[3][i], win[2][i], acc);
+        out[i] = apply_phi(acc, phi);
+        win[2][i] = win[1][i];
+        win[1][i] = win[0][i];
+        win[0][i] = c[i];
+      }
+      if (tg + r < Tn) Io<T>::store(yb + (size_t)(tg + r) * rowlen, out);
+    }
   }
 }
 
