@@ -132,9 +132,10 @@ LAWCAT_API int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, cons
 
 /*
  * Measurement aid.  While both events (hipEvent_t passed as void*) are non-NULL, every prefill call
- * that runs the bf16 matrix-core path records `before` just ahead of its output-pass kernel and
- * `after` just behind it, on the call's stream, so a caller can time that kernel alone.  Pass NULLs
- * to switch it off.  Process-wide state, not thread-safe; the events stay owned by the caller.
+ * that runs the bf16 matrix-core path launches its output-pass kernel with `before` and `after` as the
+ * kernel's start and stop events (they take the kernel's own begin and end timestamps on the call's
+ * stream), so a caller can time that kernel alone with hipEventElapsedTime.  Pass NULLs to switch it
+ * off.  Process-wide state, not thread-safe; the events stay owned by the caller.
  */
 LAWCAT_API void lawcat_trace_output_pass(void* before, void* after);
 
