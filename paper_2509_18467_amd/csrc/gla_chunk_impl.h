@@ -582,37 +582,40 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
           vv[ct] = __builtin_bit_cast(bf16x8, make_uint4(r.x, r.y, r.x, r.y));
         }
         __syncthreads();  // scores and denominators of this chunk are in LDS (double-buffered by chunk parity)
-        // One query head at a time (the loop stays rolled).  Variants that interleaved the MFMA chains of
-        // two heads, or unrolled this loop, let the compiler reuse the registers of one chain's operands
-        // as LDS-load destinations while many MFMAs were still queued, and gave results that varied from
-        // run to run on gfx950; this shape is the one the repeated-run GPU test holds bit-stable.
-#pragma unroll 1
-        for (int hh = 0; hh < GR; ++hh) {
-          bf16x8 qb[G::KS];
+        // Query heads one at a time, operands of the next head fetched from LDS while this head's MFMA chain
+        // runs.  Order matters on gfx950: a load may only target registers whose last MFMA reader has
+        // completed.  Here the loads for head h + 1 are issued BEFORE the MFMAs of head h, into the registers
+        // that head h - 1 used, and head h - 1's chain was waited for by its own epilogue (MFMAs complete in
+        // order); scheduling barriers keep the compiler from moving a load below a later MFMA.  Variants that
+        // issued the loads after queued MFMAs (two interleaved chains, an unrolled loop) gave results that
+        // varied from run to run; the repeated-run GPU test guards this shape.
+        struct HeadOps { bf16x8 qb[G::KS]; bf16x8 pp; float den; };
+        auto load_ops = [&](int hh, HeadOps& o) {
 #pragma unroll
           for (int ks = 0; ks < G::KS; ++ks) {
             const unsigned char* p = smem + G::kQp + (hh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
             const uint2 lo = *reinterpret_cast<const uint2*>(p);
             const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
-            qb[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+            o.qb[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
           }
           // scores as one k = 32 operand: slots 0..3 the high parts, 4..7 the residuals of this lane's 4 keys
-          const unsigned char* ps = smem + G::kPs + ((mc & 1) * GR + hh) * 1024 + l * 16;
-          const bf16x8 pp = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(ps));
-          // o^T[dv][query] = S^T (q (.) E)^T + [V|1]^T P^T
+          o.pp = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(smem + G::kPs + ((mc & 1) * GR + hh) * 1024 + l * 16));
+          o.den = *reinterpret_cast<const float*>(smem + G::kDn + (((mc & 1) * GR + hh) * 16 + n) * 4);
+        };
+        auto do_head = [&](int hh, const HeadOps& o) {
+          // o^T[dv][query] = S^T (q (.) E)^T + [V,V]^T [P_hi;P_lo]^T
           floatx4 oacc[G::CT];
 #pragma unroll
           for (int ct = 0; ct < G::CT; ++ct) {
             floatx4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < G::KS; ++ks)
-              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], qb[ks], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[ct], pp, acc, 0, 0, 0);
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], o.qb[ks], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[ct], o.pp, acc, 0, 0, 0);
             oacc[ct] = acc;
           }
           const int tok = tq + n;
-          const float den = *reinterpret_cast<const float*>(smem + G::kDn + (((mc & 1) * GR + hh) * 16 + n) * 4);
-          const float rden = fast_rcp(den);
+          const float rden = fast_rcp(o.den);
           if (tok < s1) {
             bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * GR + hh) * D;
 #pragma unroll
@@ -622,7 +625,24 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
               *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
             }
             if (a.den_out != nullptr && w == 0 && g4 == 0)
-              a.den_out[((size_t)b * T + tok) * a.Hq + hk * GR + hh] = den;
+              a.den_out[((size_t)b * T + tok) * a.Hq + hk * GR + hh] = o.den;
+          }
+        };
+        HeadOps opA, opB;
+        load_ops(0, opA);
+        if (GR == 1) {
+          do_head(0, opA);
+        } else {
+#pragma unroll 1
+          for (int h0 = 0; h0 < GR; h0 += 2) {
+            load_ops(h0 + 1, opB);
+            __builtin_amdgcn_sched_barrier(0);
+            do_head(h0, opA);
+            __builtin_amdgcn_sched_barrier(0);
+            if (h0 + 2 < GR) load_ops(h0 + 2, opA);
+            __builtin_amdgcn_sched_barrier(0);
+            do_head(h0 + 1, opB);
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
       }
