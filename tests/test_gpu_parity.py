@@ -173,6 +173,17 @@ def test_gla_prefill_gate_scale_and_eps(oracle):
     assert H.rel_rms_err(got["S"], ref["S"]) < 1e-5
 
 
+@pytest.mark.parametrize("d,gate_scale,eps", [(64, 0.25, 0.5), (128, 0.25, 0.0), (64, 2.0, 1e-3)])
+def test_layer_prefill_bf16_gate_scale_and_eps(oracle, d, gate_scale, eps):
+    """The matrix-core path with a gate temperature other than 1 (general log2/exp2 gate code) and eps > 0."""
+    wl = Workload(f"gs{gate_scale}d{d}", 2, 523, 8, 2, d, 4, "bf16")
+    x = make_inputs(wl, seed=11, halo=True, state=True)
+    got = H.run_layer_prefill(wl, x, feature_map=1, gate_scale=gate_scale, eps=eps)
+    ref = oracle.layer_prefill(x["Q"], x["K"], x["V"], x["G"], x["wq"], x["wk"], 1, gate_scale, eps,
+                               x["S0"], x["z0"], x["q_halo"], x["k_halo"])
+    _check_prefill(got, ref, wl, 1, f"layer_prefill[{wl.name},eps={eps}]")
+
+
 # ------------------------------------------------------------------ fused layer, the five graded shapes
 @pytest.mark.parametrize("name,T,phi,extras", [
     ("tiny", None, 1, False), ("tiny", None, 0, False), ("tiny", 203, 1, True),
