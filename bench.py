@@ -201,6 +201,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--side-ops", action="store_true", help="also time lawcat_conv1d_causal and lawcat_gla_step alone")
     ap.add_argument("--segment", type=int, default=0, help="tokens per segment (0 = the library's choice)")
+    ap.add_argument("--curve", action="store_true",
+                    help="also time both layer shapes at T = 8K .. 128K (reported under 'curve')")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -254,6 +256,20 @@ def main():
             del r2
             torch.cuda.empty_cache()
         out["sweep"] = sweep
+    if args.curve:
+        import torch
+        from dataclasses import replace
+        curve = {}
+        for base in ("llama1b_32k", "mistral7b_16k"):
+            for T in (8192, 16384, 32768, 65536, 131072):
+                w2 = replace(WORKLOADS[base], T=T, name=f"{base.split('_')[0]}@{T}")
+                r2 = run_workload(w2, max(5, args.steps // 3), max(2, args.warmup // 3), args.feature_map)
+                curve[w2.name] = {"tokens_per_s": r2["tokens_per_s"], "ms_per_step": r2["ms_per_step"],
+                                  "kernel_ms": r2["kernel_ms"],
+                                  "whole_step_frac": r2["bytes_step"] / (r2["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                del r2
+                torch.cuda.empty_cache()
+        out["curve"] = curve
     if args.side_ops:
         out["side_ops"] = run_side_ops(wl)
     if not args.no_cpu:
