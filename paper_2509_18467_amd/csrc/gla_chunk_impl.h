@@ -8,14 +8,15 @@
 //   num_t = (q_t (.) E_t) S_start + sum_{i<=t} [(q_t (.) E_t) . (k_i / E_i)] v_i
 //   den_t = (q_t (.) E_t) z_start + sum_{i<=t} [(q_t (.) E_t) . (k_i / E_i)]
 // and the state after the chunk is S_end = diag(E_last) S_start + sum_i (k_i E_last/E_i)^T v_i.
-// All four products are bf16 MFMAs with fp32 accumulation.  The normalizer rides along as 16
-// extra value columns that are all ones, so num and den come out of the same MFMAs and the
-// division needs no cross-lane traffic.
+// All the products are bf16 MFMAs with fp32 accumulation.  The normalizer z is carried as one more
+// (replicated) column tile of the state, updated by the same MFMAs against an all-ones value operand;
+// den_t is computed once per query head, by the wave that computes that head's scores, and shared
+// through LDS.
 //
 // Parallel decomposition.  One team of d/16 waves (one per 16 value columns) owns one (batch,
-// kv head) and one segment of the sequence, and walks it 16 tokens at a time with the [dk x (dv+16)] state in
-// MFMA accumulators; the query heads of the group share k, v, the decay and the state.  With
-// more than one segment a first pass computes each segment's state contribution and total
+// kv head) and one segment of the sequence, and walks it 16 tokens at a time with its [dk x (16+16)]
+// slice of the state in MFMA accumulators; the query heads of the group share k, v, the decay and the
+// state.  With more than one segment a first pass computes each segment's state contribution and total
 // decay, a small scan turns them into segment start states, and the output pass starts from
 // those.
 //
@@ -526,7 +527,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
                                                         (kChunk * mc + 4 * g4) * 2);
         vfrag[ct] = __builtin_bit_cast(short4v, r);
       }
-      vfrag[G::CT] = short4v{0x3F80, 0x3F80, 0x3F80, 0x3F80};  // ones: the normalizer columns
+      vfrag[G::CT] = short4v{0x3F80, 0x3F80, 0x3F80, 0x3F80};  // ones: the state update of the normalizer z
 
       if (OUTPUT) {
         // state as bf16 A-fragments: rows = value columns, k = key channels {4 g4 + i, 16 + 4 g4 + i} of each 32;
