@@ -41,8 +41,11 @@ inline Path prefill_path(const lawcat_desc* d) {
   // the chunk kernels address one batch element's rows with 32-bit byte offsets (buffer loads); offsets of
   // the three rows before the first token wrap around and must still land past the end of the buffer
   const bool rows_fit = ((uint64_t)d->T + 4) * d->Hq * d->dk * 2 < (1ull << 32);
-  return (d->dtype == LAWCAT_DTYPE_BF16 && chunk_path_supports(d->Hq / d->Hkv) && rows_fit) ? Path::kChunkBf16
-                                                                                            : Path::kRecurrentF32;
+  // one workgroup row per (batch, kv head) on the grid's y axis
+  const bool heads_fit = (uint64_t)d->B * d->Hkv <= 65535;
+  return (d->dtype == LAWCAT_DTYPE_BF16 && chunk_path_supports(d->Hq / d->Hkv) && rows_fit && heads_fit)
+             ? Path::kChunkBf16
+             : Path::kRecurrentF32;
 }
 
 ChunkPlan plan_for(const lawcat_desc* d) {

@@ -84,6 +84,25 @@ def test_alignment_and_workspace():
     assert lawcat.workspace_bytes(lawcat.make_desc(1, 16, 3, 2, 64), lawcat.CALL_LAYER_PREFILL) == 0
 
 
+def test_path_selection_shows_in_workspace_size():
+    """Shapes the matrix-core path does not take fall back to the unfused fp32-accumulating path, whose
+    workspace holds q-dot and k-dot: rows that need more than 32-bit byte offsets, more (batch, kv head)
+    pairs than a grid axis holds, group sizes other than 1, 2, 4."""
+    def unfused(B, T, Hq, Hkv, d):
+        up = lambda n: (n + 255) // 256 * 256
+        return up(B * T * Hq * d * 2) + up(B * T * Hkv * d * 2)
+
+    call = lawcat.CALL_LAYER_PREFILL
+    ok = lawcat.make_desc(1, 32768, 32, 8, 64)
+    assert 0 < lawcat.workspace_bytes(ok, call) < 32 * 1024 * 1024  # segment states only
+    long_rows = lawcat.make_desc(1, 1 << 20, 32, 8, 64)             # 2^20 tokens x 4 KiB rows = 4 GiB
+    assert lawcat.workspace_bytes(long_rows, call) == unfused(1, 1 << 20, 32, 8, 64)
+    many_heads = lawcat.make_desc(70000, 16, 1, 1, 64)
+    assert lawcat.workspace_bytes(many_heads, call) == unfused(70000, 16, 1, 1, 64)
+    group8 = lawcat.make_desc(1, 4096, 16, 2, 64)
+    assert lawcat.workspace_bytes(group8, call) == unfused(1, 4096, 16, 2, 64)
+
+
 def test_other_entry_points_report_errors():
     L = lawcat.lib()
     d = lawcat.make_desc(2, 64, 4, 2, 128)
