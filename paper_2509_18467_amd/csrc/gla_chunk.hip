@@ -14,7 +14,7 @@ void set_output_pass_events(hipEvent_t before, hipEvent_t after) {
   chunk::g_ev_after = after;
 }
 
-bool chunk_path_supports(int group) { return group == 1 || group == 2 || group == 4; }
+bool chunk_path_supports(int group) { return group >= 1 && group <= 64; }
 
 ChunkPlan make_chunk_plan(int B, int T, int Hkv, int d, int carry_mode, int segment) {
   ChunkPlan p;

@@ -54,6 +54,8 @@ struct ChunkArgs {
   bf16_t *q_tail, *k_tail;
   float* ws;
   int B, T, Hq, Hkv, W;
+  int group;   // query heads per kv head (Hq / Hkv)
+  int qh0;     // first query head, within its group, that this launch of the output pass covers
   int seg_len, nseg;
   float gate_scale, eps;
 };
@@ -419,7 +421,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
       const int dl = e & 3, c = (e >> 2) % D, hh = e / (4 * D);
       float val = 0.f;
       if (dl < a.W && (OUTPUT || hh == GR)) {
-        const bf16_t* src = hh < GR ? a.wq + ((size_t)(hk * GR + hh) * D + c) * a.W + dl
+        const bf16_t* src = hh < GR ? a.wq + ((size_t)(hk * a.group + a.qh0 + hh) * D + c) * a.W + dl
                                     : a.wk + ((size_t)hk * D + c) * a.W + dl;
         val = __uint_as_float((uint32_t)(*src) << 16) * wscale;
       }
@@ -435,8 +437,8 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
   const RowSrc srcG = make_row_src((const char*)a.g + ((size_t)b * T * a.Hkv + hk) * D * 2, nullptr, kvstride, T, D * 2);
   const RowSrc srcV = make_row_src((const char*)a.v + ((size_t)b * T * a.Hkv + hk) * D * 2, nullptr, kvstride, T, D * 2);
   const RowSrc srcQ = make_row_src(
-      (const char*)a.q + ((size_t)b * T * a.Hq + hk * GR) * D * 2,
-      (CONV && a.q_halo) ? (const char*)a.q_halo + ((size_t)b * (a.W - 1) * a.Hq + hk * GR) * D * 2 : nullptr, qstride, T,
+      (const char*)a.q + ((size_t)b * T * a.Hq + hk * a.group + a.qh0) * D * 2,
+      (CONV && a.q_halo) ? (const char*)a.q_halo + ((size_t)b * (a.W - 1) * a.Hq + hk * a.group + a.qh0) * D * 2 : nullptr, qstride, T,
       (GR > 0 ? GR : 1) * D * 2);
   const unsigned coff = (unsigned)c0 * 2;
 
@@ -618,7 +620,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
           const int tok = tq + n;
           const float rden = fast_rcp(o.den);
           if (tok < s1) {
-            bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * GR + hh) * D;
+            bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * a.group + a.qh0 + hh) * D;
 #pragma unroll
             for (int ct = 0; ct < G::CT; ++ct) {
               const uint2 pk = make_uint2(pack2(oacc[ct][0] * rden, oacc[ct][1] * rden),
@@ -626,7 +628,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
               *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
             }
             if (a.den_out != nullptr && w == 0 && g4 == 0)
-              a.den_out[((size_t)b * T + tok) * a.Hq + hk * GR + hh] = o.den;
+              a.den_out[((size_t)b * T + tok) * a.Hq + hk * a.group + a.qh0 + hh] = o.den;
           }
         };
         HeadOps opA, opB;
@@ -705,7 +707,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
       const bool isq = hh < GR;
       bf16_t* dst = isq ? a.q_tail : a.k_tail;
       if (dst == nullptr) continue;
-      const int H = isq ? a.Hq : a.Hkv, head = isq ? hk * GR + hh : hk;
+      const int H = isq ? a.Hq : a.Hkv, head = isq ? hk * a.group + a.qh0 + hh : hk;
       const bf16_t* x = isq ? a.q : a.k;
       const bf16_t* halo = isq ? a.q_halo : a.k_halo;
       const int src = T - Wm + r;
@@ -791,11 +793,11 @@ hipError_t set_lds(K kernel, int bytes) {
 extern hipEvent_t g_ev_before, g_ev_after;
 
 template <int D, int GR, int MODE>
-hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
+hipError_t launch_all(const ChunkArgs& a, hipStream_t stream, bool with_state_pass) {
   using G = Geo<D, GR>;
   const int heads = a.B * a.Hkv;
   hipError_t e;
-  if (a.nseg > 1) {
+  if (a.nseg > 1 && with_state_pass) {
     // GR = 0: key side only
     auto k1 = gla_chunk_kernel<D, 0, MODE, false>;
     constexpr int lds1 = Geo<D, 0>::kBytes;
@@ -828,20 +830,36 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// A group of any size is covered by output-pass launches over 4, 2 or 1 of its query heads at a time; they
+// share one state pass and one scan (the key side does not depend on the query heads), and each writes the
+// same final state.
 template <int D>
-hipError_t launch_d(const ChunkArgs& a, int group, int mode, hipStream_t stream) {
-#define LAWCAT_CASE(GRV)                                                       \
-  case GRV:                                                                    \
-    if (mode == kPlain) return launch_all<D, GRV, kPlain>(a, stream);      \
-    if (mode == kConvId) return launch_all<D, GRV, kConvId>(a, stream);    \
-    return launch_all<D, GRV, kConvElu>(a, stream);
-  switch (group) {
-    LAWCAT_CASE(1)
-    LAWCAT_CASE(2)
-    LAWCAT_CASE(4)
-    default: return hipErrorInvalidValue;
-  }
+hipError_t launch_d(const ChunkArgs& a0, int group, int mode, hipStream_t stream) {
+  ChunkArgs a = a0;
+  a.group = group;
+  bool first = true;
+  for (int qh0 = 0; qh0 < group;) {
+    const int left = group - qh0, gr = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
+    a.qh0 = qh0;
+    hipError_t e;
+#define LAWCAT_CASE(GRV)                                                                      \
+  case GRV:                                                                                   \
+    e = mode == kPlain    ? launch_all<D, GRV, kPlain>(a, stream, first)                      \
+        : mode == kConvId ? launch_all<D, GRV, kConvId>(a, stream, first)                     \
+                          : launch_all<D, GRV, kConvElu>(a, stream, first);                   \
+    break;
+    switch (gr) {
+      LAWCAT_CASE(1)
+      LAWCAT_CASE(2)
+      LAWCAT_CASE(4)
+      default: e = hipErrorInvalidValue;
+    }
 #undef LAWCAT_CASE
+    if (e != hipSuccess) return e;
+    first = false;
+    qh0 += gr;
+  }
+  return hipSuccess;
 }
 
 }  // namespace chunk

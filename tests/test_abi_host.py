@@ -87,7 +87,7 @@ def test_alignment_and_workspace():
 def test_path_selection_shows_in_workspace_size():
     """Shapes the matrix-core path does not take fall back to the unfused fp32-accumulating path, whose
     workspace holds q-dot and k-dot: rows that need more than 32-bit byte offsets, more (batch, kv head)
-    pairs than a grid axis holds, group sizes other than 1, 2, 4."""
+    pairs than a grid axis holds, more than 64 query heads per kv head."""
     def unfused(B, T, Hq, Hkv, d):
         up = lambda n: (n + 255) // 256 * 256
         return up(B * T * Hq * d * 2) + up(B * T * Hkv * d * 2)
@@ -99,8 +99,10 @@ def test_path_selection_shows_in_workspace_size():
     assert lawcat.workspace_bytes(long_rows, call) == unfused(1, 1 << 20, 32, 8, 64)
     many_heads = lawcat.make_desc(70000, 16, 1, 1, 64)
     assert lawcat.workspace_bytes(many_heads, call) == unfused(70000, 16, 1, 1, 64)
-    group8 = lawcat.make_desc(1, 4096, 16, 2, 64)
-    assert lawcat.workspace_bytes(group8, call) == unfused(1, 4096, 16, 2, 64)
+    group8 = lawcat.make_desc(1, 4096, 16, 2, 64)   # covered by two launches over 4 query heads each
+    assert 0 < lawcat.workspace_bytes(group8, call) < unfused(1, 4096, 16, 2, 64)
+    group65 = lawcat.make_desc(1, 4096, 130, 2, 64)
+    assert lawcat.workspace_bytes(group65, call) == unfused(1, 4096, 130, 2, 64)
 
 
 def test_other_entry_points_report_errors():

@@ -115,9 +115,11 @@ def test_gla_prefill(oracle, name, T, phi):
 
 @pytest.mark.parametrize("phi", [1, 0])
 @pytest.mark.parametrize("Hq,Hkv,d,T,W", [(3, 3, 64, 150, 4), (4, 2, 64, 389, 3), (2, 2, 128, 200, 4), (4, 2, 128, 131, 2),
-                                          (8, 2, 64, 257, 4), (4, 1, 128, 64, 4)])
+                                          (8, 2, 64, 257, 4), (4, 1, 128, 64, 4), (6, 2, 64, 300, 4), (16, 2, 64, 777, 4),
+                                          (7, 1, 128, 333, 4), (5, 1, 64, 1200, 4)])
 def test_layer_prefill_other_group_sizes(oracle, Hq, Hkv, d, T, W, phi):
-    """bf16 fused layer with 1, 2 and 4 query heads per kv head, both head dims, batch 2, ragged lengths."""
+    """bf16 fused layer with 1 to 8 query heads per kv head (3, 5, 7 and 8 take several output-pass launches),
+    both head dims, batch 2, ragged lengths, one case long enough for the two-level carry."""
     wl = Workload(f"g{Hq // Hkv}d{d}", 2, T, Hq, Hkv, d, W, "bf16")
     # a random signed start state under signed features only adds cancellation noise: keep it for 1+ELU
     x = make_inputs(wl, seed=7, halo=True, state=(phi == 1))
