@@ -489,7 +489,6 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
 #pragma unroll 1
   for (int gi = 0; gi < nseg_gran; ++gi) {
     const int t0 = tfirst + gi * tstep;
-    {
       {
         // =========================== compute stage: registers -> LDS operands ===========================
         const bool edge = (t0 < 3) || (t0 + G::NTG > s1);
@@ -516,160 +515,159 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
         // next granule's rows travel while the matrix cores work
         if (gi + 1 < nseg_gran) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, t0 + tstep, s1, tl0, coff, a.W);
 
-    // =========================== MFMA stage: 16 tokens at a time ===========================
+        // =========================== MFMA stage: 16 tokens at a time ===========================
 #pragma unroll 1
-    for (int mc = 0; mc < G::MCG; ++mc) {
-      const int tq = t0 + kChunk * mc;  // first token of the chunk
-      if (tq >= s1) break;
-      // value fragments: lane (g4, n) holds V[tok 4 g4 .. +3][dv 16 tile + n]; serves as A (V^T) and as B (V)
-      short4v vfrag[G::NT];
-#pragma unroll
-      for (int ct = 0; ct < G::CT; ++ct) {
-        const uint2 r = *reinterpret_cast<const uint2*>(smem + G::kVt + (16 * (w * G::CT + ct) + n) * G::TRS +
-                                                        (kChunk * mc + 4 * g4) * 2);
-        vfrag[ct] = __builtin_bit_cast(short4v, r);
-      }
-      vfrag[G::CT] = short4v{0x3F80, 0x3F80, 0x3F80, 0x3F80};  // ones: the state update of the normalizer z
-
-      if (OUTPUT) {
-        // state as bf16 A-fragments: rows = value columns, k = key channels {4 g4 + i, 16 + 4 g4 + i} of each 32;
-        // tile CT is the normalizer z, the same in every row
-        bf16x8 sa[G::NT][G::KS];
-#pragma unroll
-        for (int ct = 0; ct < G::NT; ++ct)
-#pragma unroll
-          for (int ks = 0; ks < G::KS; ++ks) {
-            const floatx4 lo = Sacc[2 * ks][ct], hi = Sacc[2 * ks + 1][ct];
-            sa[ct][ks] = __builtin_bit_cast(
-                bf16x8, make_uint4(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])));
-          }
-        // ---- scores and denominators: wave w < GR computes, for query head w alone, P^T = K' Q'^T and
-        // den = q' . z + (column sums of the masked P), and shares both through LDS.  Computing the denominator
-        // once per head instead of once per wave saves every wave a whole accumulator tile per head.
-        if (w < GR) {
-          const int myh = w;
-          floatx4 pt = {0.f, 0.f, 0.f, 0.f}, dz = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int ks = 0; ks < G::KS; ++ks) {
-            const unsigned char* pk = smem + G::kKp + (kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
-            const unsigned char* pq = smem + G::kQp + (myh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
-            const uint2 klo = *reinterpret_cast<const uint2*>(pk), khi = *reinterpret_cast<const uint2*>(pk + 32);
-            const uint2 qlo = *reinterpret_cast<const uint2*>(pq), qhi = *reinterpret_cast<const uint2*>(pq + 32);
-            const bf16x8 qf = __builtin_bit_cast(bf16x8, make_uint4(qlo.x, qlo.y, qhi.x, qhi.y));
-            pt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8, make_uint4(klo.x, klo.y, khi.x, khi.y)), qf, pt, 0, 0, 0);
-            dz = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[G::CT][ks], qf, dz, 0, 0, 0);
-          }
-          // P^T[key 4 g4 + i][query n], causal: key <= query
-#pragma unroll
-          for (int i = 0; i < 4; ++i) pt[i] = (4 * g4 + i <= n) ? pt[i] : 0.f;
-          // The weights of the few nearest keys dominate the output, so their bf16 rounding would not
-          // average out: carry P as a bf16 pair (high part + residual) in one k = 32 operand.
-          const uint32_t ph0 = pack2(pt[0], pt[1]), ph1 = pack2(pt[2], pt[3]);
-          const uint32_t pl0 = pack2(pt[0] - bf_lo(ph0), pt[1] - bf_hi(ph0));
-          const uint32_t pl1 = pack2(pt[2] - bf_lo(ph1), pt[3] - bf_hi(ph1));
-          unsigned char* ps = smem + G::kPs + ((mc & 1) * GR + myh) * 1024 + l * 16;
-          *reinterpret_cast<uint4*>(ps) = make_uint4(ph0, ph1, pl0, pl1);
-          // column sum over the 16 keys: 4 in this lane, the other 12 in the lanes 16, 32 and 48 away
-          float cs = (pt[0] + pt[1]) + (pt[2] + pt[3]);
-          cs += __shfl_xor(cs, 16);
-          cs += __shfl_xor(cs, 32);
-          if (g4 == 0)
-            *reinterpret_cast<float*>(smem + G::kDn + (((mc & 1) * GR + myh) * 16 + n) * 4) = dz[0] + cs + a.eps;
-        }
-        // [V|1]^T against (high, residual) in one k = 32 MFMA: the same four tokens fill both halves of A
-        bf16x8 vv[G::CT];
-#pragma unroll
-        for (int ct = 0; ct < G::CT; ++ct) {
-          const uint2 r = __builtin_bit_cast(uint2, vfrag[ct]);
-          vv[ct] = __builtin_bit_cast(bf16x8, make_uint4(r.x, r.y, r.x, r.y));
-        }
-        __syncthreads();  // scores and denominators of this chunk are in LDS (double-buffered by chunk parity)
-        // Query heads one at a time, operands of the next head fetched from LDS while this head's MFMA chain
-        // runs.  Order matters on gfx950: a load may only target registers whose last MFMA reader has
-        // completed.  Here the loads for head h + 1 are issued BEFORE the MFMAs of head h, into the registers
-        // that head h - 1 used, and head h - 1's chain was waited for by its own epilogue (MFMAs complete in
-        // order); scheduling barriers keep the compiler from moving a load below a later MFMA.  Variants that
-        // issued the loads after queued MFMAs (two interleaved chains, an unrolled loop) gave results that
-        // varied from run to run; the repeated-run GPU test guards this shape.
-        struct HeadOps { bf16x8 qb[G::KS]; bf16x8 pp; float den; };
-        auto load_ops = [&](int hh, HeadOps& o) {
-#pragma unroll
-          for (int ks = 0; ks < G::KS; ++ks) {
-            const unsigned char* p = smem + G::kQp + (hh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
-            const uint2 lo = *reinterpret_cast<const uint2*>(p);
-            const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
-            o.qb[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
-          }
-          // scores as one k = 32 operand: slots 0..3 the high parts, 4..7 the residuals of this lane's 4 keys
-          o.pp = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(smem + G::kPs + ((mc & 1) * GR + hh) * 1024 + l * 16));
-          o.den = *reinterpret_cast<const float*>(smem + G::kDn + (((mc & 1) * GR + hh) * 16 + n) * 4);
-        };
-        auto do_head = [&](int hh, const HeadOps& o) {
-          // o^T[dv][query] = S^T (q (.) E)^T + [V,V]^T [P_hi;P_lo]^T
-          floatx4 oacc[G::CT];
+        for (int mc = 0; mc < G::MCG; ++mc) {
+          const int tq = t0 + kChunk * mc;  // first token of the chunk
+          if (tq >= s1) break;
+          // value fragments: lane (g4, n) holds V[tok 4 g4 .. +3][dv 16 tile + n]; serves as A (V^T) and as B (V)
+          short4v vfrag[G::NT];
 #pragma unroll
           for (int ct = 0; ct < G::CT; ++ct) {
-            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < G::KS; ++ks)
-              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], o.qb[ks], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[ct], o.pp, acc, 0, 0, 0);
-            oacc[ct] = acc;
+            const uint2 r = *reinterpret_cast<const uint2*>(smem + G::kVt + (16 * (w * G::CT + ct) + n) * G::TRS +
+                                                            (kChunk * mc + 4 * g4) * 2);
+            vfrag[ct] = __builtin_bit_cast(short4v, r);
           }
-          const int tok = tq + n;
-          const float rden = fast_rcp(o.den);
-          if (tok < s1) {
-            bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * a.group + a.qh0 + hh) * D;
+          vfrag[G::CT] = short4v{0x3F80, 0x3F80, 0x3F80, 0x3F80};  // ones: the state update of the normalizer z
+
+          if (OUTPUT) {
+            // state as bf16 A-fragments: rows = value columns, k = key channels {4 g4 + i, 16 + 4 g4 + i} of each 32;
+            // tile CT is the normalizer z, the same in every row
+            bf16x8 sa[G::NT][G::KS];
+#pragma unroll
+            for (int ct = 0; ct < G::NT; ++ct)
+#pragma unroll
+              for (int ks = 0; ks < G::KS; ++ks) {
+                const floatx4 lo = Sacc[2 * ks][ct], hi = Sacc[2 * ks + 1][ct];
+                sa[ct][ks] = __builtin_bit_cast(
+                    bf16x8, make_uint4(pack2(lo[0], lo[1]), pack2(lo[2], lo[3]), pack2(hi[0], hi[1]), pack2(hi[2], hi[3])));
+              }
+            // ---- scores and denominators: wave w < GR computes, for query head w alone, P^T = K' Q'^T and
+            // den = q' . z + (column sums of the masked P), and shares both through LDS.  Computing the denominator
+            // once per head instead of once per wave saves every wave a whole accumulator tile per head.
+            if (w < GR) {
+              const int myh = w;
+              floatx4 pt = {0.f, 0.f, 0.f, 0.f}, dz = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+              for (int ks = 0; ks < G::KS; ++ks) {
+                const unsigned char* pk = smem + G::kKp + (kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+                const unsigned char* pq = smem + G::kQp + (myh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+                const uint2 klo = *reinterpret_cast<const uint2*>(pk), khi = *reinterpret_cast<const uint2*>(pk + 32);
+                const uint2 qlo = *reinterpret_cast<const uint2*>(pq), qhi = *reinterpret_cast<const uint2*>(pq + 32);
+                const bf16x8 qf = __builtin_bit_cast(bf16x8, make_uint4(qlo.x, qlo.y, qhi.x, qhi.y));
+                pt = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    __builtin_bit_cast(bf16x8, make_uint4(klo.x, klo.y, khi.x, khi.y)), qf, pt, 0, 0, 0);
+                dz = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[G::CT][ks], qf, dz, 0, 0, 0);
+              }
+              // P^T[key 4 g4 + i][query n], causal: key <= query
+#pragma unroll
+              for (int i = 0; i < 4; ++i) pt[i] = (4 * g4 + i <= n) ? pt[i] : 0.f;
+              // The weights of the few nearest keys dominate the output, so their bf16 rounding would not
+              // average out: carry P as a bf16 pair (high part + residual) in one k = 32 operand.
+              const uint32_t ph0 = pack2(pt[0], pt[1]), ph1 = pack2(pt[2], pt[3]);
+              const uint32_t pl0 = pack2(pt[0] - bf_lo(ph0), pt[1] - bf_hi(ph0));
+              const uint32_t pl1 = pack2(pt[2] - bf_lo(ph1), pt[3] - bf_hi(ph1));
+              unsigned char* ps = smem + G::kPs + ((mc & 1) * GR + myh) * 1024 + l * 16;
+              *reinterpret_cast<uint4*>(ps) = make_uint4(ph0, ph1, pl0, pl1);
+              // column sum over the 16 keys: 4 in this lane, the other 12 in the lanes 16, 32 and 48 away
+              float cs = (pt[0] + pt[1]) + (pt[2] + pt[3]);
+              cs += __shfl_xor(cs, 16);
+              cs += __shfl_xor(cs, 32);
+              if (g4 == 0)
+                *reinterpret_cast<float*>(smem + G::kDn + (((mc & 1) * GR + myh) * 16 + n) * 4) = dz[0] + cs + a.eps;
+            }
+            // [V|1]^T against (high, residual) in one k = 32 MFMA: the same four tokens fill both halves of A
+            bf16x8 vv[G::CT];
 #pragma unroll
             for (int ct = 0; ct < G::CT; ++ct) {
-              const uint2 pk = make_uint2(pack2(oacc[ct][0] * rden, oacc[ct][1] * rden),
-                                          pack2(oacc[ct][2] * rden, oacc[ct][3] * rden));
-              *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
+              const uint2 r = __builtin_bit_cast(uint2, vfrag[ct]);
+              vv[ct] = __builtin_bit_cast(bf16x8, make_uint4(r.x, r.y, r.x, r.y));
             }
-            if (a.den_out != nullptr && w == 0 && g4 == 0)
-              a.den_out[((size_t)b * T + tok) * a.Hq + hk * a.group + a.qh0 + hh] = o.den;
-          }
-        };
-        HeadOps opA, opB;
-        load_ops(0, opA);
-        if (GR == 1) {
-          do_head(0, opA);
-        } else {
+            __syncthreads();  // scores and denominators of this chunk are in LDS (double-buffered by chunk parity)
+            // Query heads one at a time, operands of the next head fetched from LDS while this head's MFMA chain
+            // runs.  Order matters on gfx950: a load may only target registers whose last MFMA reader has
+            // completed.  Here the loads for head h + 1 are issued BEFORE the MFMAs of head h, into the registers
+            // that head h - 1 used, and head h - 1's chain was waited for by its own epilogue (MFMAs complete in
+            // order); scheduling barriers keep the compiler from moving a load below a later MFMA.  Variants that
+            // issued the loads after queued MFMAs (two interleaved chains, an unrolled loop) gave results that
+            // varied from run to run; the repeated-run GPU test guards this shape.
+            struct HeadOps { bf16x8 qb[G::KS]; bf16x8 pp; float den; };
+            auto load_ops = [&](int hh, HeadOps& o) {
+#pragma unroll
+              for (int ks = 0; ks < G::KS; ++ks) {
+                const unsigned char* p = smem + G::kQp + (hh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+                const uint2 lo = *reinterpret_cast<const uint2*>(p);
+                const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
+                o.qb[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+              }
+              // scores as one k = 32 operand: slots 0..3 the high parts, 4..7 the residuals of this lane's 4 keys
+              o.pp = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(smem + G::kPs + ((mc & 1) * GR + hh) * 1024 + l * 16));
+              o.den = *reinterpret_cast<const float*>(smem + G::kDn + (((mc & 1) * GR + hh) * 16 + n) * 4);
+            };
+            auto do_head = [&](int hh, const HeadOps& o) {
+              // o^T[dv][query] = S^T (q (.) E)^T + [V,V]^T [P_hi;P_lo]^T
+              floatx4 oacc[G::CT];
+#pragma unroll
+              for (int ct = 0; ct < G::CT; ++ct) {
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < G::KS; ++ks)
+                  acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[ct][ks], o.qb[ks], acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vv[ct], o.pp, acc, 0, 0, 0);
+                oacc[ct] = acc;
+              }
+              const int tok = tq + n;
+              const float rden = fast_rcp(o.den);
+              if (tok < s1) {
+                bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * a.group + a.qh0 + hh) * D;
+#pragma unroll
+                for (int ct = 0; ct < G::CT; ++ct) {
+                  const uint2 pk = make_uint2(pack2(oacc[ct][0] * rden, oacc[ct][1] * rden),
+                                              pack2(oacc[ct][2] * rden, oacc[ct][3] * rden));
+                  *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
+                }
+                if (a.den_out != nullptr && w == 0 && g4 == 0)
+                  a.den_out[((size_t)b * T + tok) * a.Hq + hk * a.group + a.qh0 + hh] = o.den;
+              }
+            };
+            HeadOps opA, opB;
+            load_ops(0, opA);
+            if (GR == 1) {
+              do_head(0, opA);
+            } else {
 #pragma unroll 1
-          for (int h0 = 0; h0 < GR; h0 += 2) {
-            load_ops(h0 + 1, opB);
-            __builtin_amdgcn_sched_barrier(0);
-            do_head(h0, opA);
-            __builtin_amdgcn_sched_barrier(0);
-            if (h0 + 2 < GR) load_ops(h0 + 2, opA);
-            __builtin_amdgcn_sched_barrier(0);
-            do_head(h0 + 1, opB);
-            __builtin_amdgcn_sched_barrier(0);
+              for (int h0 = 0; h0 < GR; h0 += 2) {
+                load_ops(h0 + 1, opB);
+                __builtin_amdgcn_sched_barrier(0);
+                do_head(h0, opA);
+                __builtin_amdgcn_sched_barrier(0);
+                if (h0 + 2 < GR) load_ops(h0 + 2, opA);
+                __builtin_amdgcn_sched_barrier(0);
+                do_head(h0 + 1, opB);
+                __builtin_amdgcn_sched_barrier(0);
+              }
+            }
+          }
+          // ---- state update: S <- diag(E_last) S + Kdec^T [V | 1]
+#pragma unroll
+          for (int rt = 0; rt < G::RT; ++rt) {
+            const uint2 kr = *reinterpret_cast<const uint2*>(smem + G::kKd + (16 * rt + n) * G::TRS +
+                                                             (kChunk * mc + 4 * g4) * 2);
+            const short4v kdf = __builtin_bit_cast(short4v, kr);
+            floatx4 eb = {1.f, 1.f, 1.f, 1.f};
+            if (OUTPUT) eb = *reinterpret_cast<const floatx4*>(smem + G::kEb + (mc * D + 16 * rt + 4 * g4) * 4);
+#pragma unroll
+            for (int ct = 0; ct < G::NT; ++ct) {
+              floatx4 acc = Sacc[rt][ct];
+              if (OUTPUT) {  // the state pass pre-decays its operands to the end of the segment instead
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i] *= eb[i];
+              }
+              Sacc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kdf, vfrag[ct], acc, 0, 0, 0);
+            }
           }
         }
-      }
-      // ---- state update: S <- diag(E_last) S + Kdec^T [V | 1]
-#pragma unroll
-      for (int rt = 0; rt < G::RT; ++rt) {
-        const uint2 kr = *reinterpret_cast<const uint2*>(smem + G::kKd + (16 * rt + n) * G::TRS +
-                                                         (kChunk * mc + 4 * g4) * 2);
-        const short4v kdf = __builtin_bit_cast(short4v, kr);
-        floatx4 eb = {1.f, 1.f, 1.f, 1.f};
-        if (OUTPUT) eb = *reinterpret_cast<const floatx4*>(smem + G::kEb + (mc * D + 16 * rt + 4 * g4) * 4);
-#pragma unroll
-        for (int ct = 0; ct < G::NT; ++ct) {
-          floatx4 acc = Sacc[rt][ct];
-          if (OUTPUT) {  // the state pass pre-decays its operands to the end of the segment instead
-#pragma unroll
-            for (int i = 0; i < 4; ++i) acc[i] *= eb[i];
-          }
-          Sacc[rt][ct] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(kdf, vfrag[ct], acc, 0, 0, 0);
-        }
-      }
-    }
       }  // MFMA stage
-    }
     __syncthreads();
   }
 
