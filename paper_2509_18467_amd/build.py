@@ -18,8 +18,12 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    objdir = os.path.join(_HERE, "_build")
+def build(verbose: bool = False, out: str | None = None) -> str:
+    """Compile and link.  `out` (or the environment variable LAWCAT_LIB_OUT) names another output file, with its
+    own object directory beside it, so that an experimental build never replaces the in-tree library that the
+    tests and bench.py load."""
+    out = out or os.environ.get("LAWCAT_LIB_OUT") or LIB
+    objdir = os.path.join(_HERE, "_build") if out == LIB else out + ".objs"
     os.makedirs(objdir, exist_ok=True)
 
     def compile_one(src):
@@ -33,11 +37,11 @@ def build(verbose: bool = False) -> str:
 
     with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
