@@ -441,6 +441,11 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
       (CONV && a.q_halo) ? (const char*)a.q_halo + ((size_t)b * (a.W - 1) * a.Hq + hk * a.group + a.qh0) * D * 2 : nullptr, qstride, T,
       (GR > 0 ? GR : 1) * D * 2);
   const unsigned coff = (unsigned)c0 * 2;
+  // This lane's part of the LDS address of a token-major row, formed once so that the chunk loop only adds a
+  // uniform offset.  (Left to the compiler, row index times stride became a 64-bit multiply-add whose unused
+  // high half aliased a register with a prefetch in flight, and the chunk loop then began by waiting for the
+  // whole prefetch.)
+  const unsigned lrow = (unsigned)n * G::QRS + (unsigned)g4 * 8;
 
   // ---- state in accumulators: Sacc[rt][ct][i] = S[16 rt + 4 g4 + i][16 tile(ct) + n]; ct == CT holds z replicated
   floatx4 Sacc[G::RT][G::NT];
@@ -550,8 +555,8 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
               floatx4 pt = {0.f, 0.f, 0.f, 0.f}, dz = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
               for (int ks = 0; ks < G::KS; ++ks) {
-                const unsigned char* pk = smem + G::kKp + (kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
-                const unsigned char* pq = smem + G::kQp + (myh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+                const unsigned char* pk = smem + G::kKp + (kChunk * mc) * G::QRS + lrow + 64 * ks;
+                const unsigned char* pq = smem + G::kQp + (myh * G::NTG + kChunk * mc) * G::QRS + lrow + 64 * ks;
                 const uint2 klo = *reinterpret_cast<const uint2*>(pk), khi = *reinterpret_cast<const uint2*>(pk + 32);
                 const uint2 qlo = *reinterpret_cast<const uint2*>(pq), qhi = *reinterpret_cast<const uint2*>(pq + 32);
                 const bf16x8 qf = __builtin_bit_cast(bf16x8, make_uint4(qlo.x, qlo.y, qhi.x, qhi.y));
@@ -595,7 +600,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
             auto load_ops = [&](int hh, HeadOps& o) {
 #pragma unroll
               for (int ks = 0; ks < G::KS; ++ks) {
-                const unsigned char* p = smem + G::kQp + (hh * G::NTG + kChunk * mc + n) * G::QRS + (32 * ks + 4 * g4) * 2;
+                const unsigned char* p = smem + G::kQp + (hh * G::NTG + kChunk * mc) * G::QRS + lrow + 64 * ks;
                 const uint2 lo = *reinterpret_cast<const uint2*>(p);
                 const uint2 hi = *reinterpret_cast<const uint2*>(p + 32);
                 o.qb[ks] = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
