@@ -176,27 +176,20 @@ struct Kernel {
   static constexpr int NQ = OUTPUT ? GR : 1;
 
   // ---- HBM -> registers: the raw rows of the granule starting at token t0
-  // The fetch is split so that fewer registers stay occupied across the MFMA stage: gate logits,
-  // keys, values and the first NQE query heads are issued one stage ahead (PART 0); the remaining
-  // query heads are fetched inside the compute stage, one head ahead of their use (fetch_head).
-  static constexpr int NQE = (OUTPUT && D == 64) ? (NQ + 1) / 2 : 0;
-  template <int PART>
+  // Gate logits, keys and values are issued one stage ahead (under the MFMA stage); the query heads are fetched
+  // inside the compute stage, one head ahead of their use (fetch_head).  Prefetching query heads a stage ahead
+  // as well measured slower at every count tried (larger bursts into the memory pipeline, more registers live
+  // across the MFMA stage).
   __device__ static inline void fetch(Raw<NQ>& raw, const RowSrc& srcK, const RowSrc& srcG, const RowSrc& srcV,
-                                      const RowSrc& srcQ, int t0, int s1, int tl0, unsigned coff, int W) {
-    constexpr int H0 = PART == 0 ? 0 : NQE, H1 = PART == 0 ? NQE : (OUTPUT ? NQ : 0);
-    if (PART == 0) {
-      const unsigned voffkv = (unsigned)tl0 * srcK.stride + coff;
-      load_rows<false>(srcG, t0, tl0, 1, voffkv, coff, raw.g);
-      load_rows<CONV>(srcK, t0, tl0, W, voffkv, coff, raw.k);
-      load_rows<false>(srcV, t0, tl0, 1, voffkv, coff, raw.v);
-    }
-    const unsigned voffq = (unsigned)tl0 * srcQ.stride + coff;
-#pragma unroll
-    for (int hh = H0; hh < H1; ++hh) load_rows<CONV>(srcQ, t0, tl0, W, voffq + hh * D * 2, coff + hh * D * 2, raw.q[hh]);
+                                      int t0, int tl0, unsigned coff, int W) {
+    const unsigned voffkv = (unsigned)tl0 * srcK.stride + coff;
+    load_rows<false>(srcG, t0, tl0, 1, voffkv, coff, raw.g);
+    load_rows<CONV>(srcK, t0, tl0, W, voffkv, coff, raw.k);
+    load_rows<false>(srcV, t0, tl0, 1, voffkv, coff, raw.v);
   }
 
-  // One late query head (index >= NQE) of the granule at t0.
-  __device__ static inline void fetch_head(Raw<NQ>& raw, const RowSrc& srcQ, int hh, int t0, int s1, int tl0,
+  // One query head of the granule at t0.
+  __device__ static inline void fetch_head(Raw<NQ>& raw, const RowSrc& srcQ, int hh, int t0, int tl0,
                                            unsigned coff, int W) {
     load_rows<CONV>(srcQ, t0, tl0, W, (unsigned)tl0 * srcQ.stride + coff + hh * D * 2, coff + hh * D * 2, raw.q[hh]);
   }
@@ -207,8 +200,8 @@ struct Kernel {
                                         const float* wl, int t0, int s1, int tl0, int c0, int mcw, int th,
                                         float gate_scale) {
     const int tok0 = t0 + tl0;
-    // late query heads are fetched one head ahead of their use
-    if (OUTPUT && NQE < NQ) fetch_head(raw, srcQ, NQE, t0, s1, tl0, coff, W);
+    // query heads are fetched one head ahead of their use
+    if (OUTPUT) fetch_head(raw, srcQ, 0, t0, tl0, coff, W);
     // keys first: conv + phi into kf, which the gate loop below scales in place by 1/E as it goes
     float kf[8][2];
     conv_phi<MODE>(raw.k, wl + ((size_t)GR * D + c0) * 4, kf);
@@ -290,7 +283,7 @@ struct Kernel {
 #pragma unroll
       for (int hh = 0; hh < NQ; ++hh) {
         __builtin_amdgcn_sched_barrier(0);
-        if (hh >= NQE && hh + 1 < NQ) fetch_head(raw, srcQ, hh + 1, t0, s1, tl0, coff, W);
+        if (hh + 1 < NQ) fetch_head(raw, srcQ, hh + 1, t0, tl0, coff, W);
         float qf[8][2];
         conv_phi<MODE>(raw.q[hh], wl + ((size_t)hh * D + c0) * 4, qf);
         unsigned char* qp = smem + G::kQp + (hh * G::NTG + tl0) * G::QRS + c0 * 2;
@@ -487,7 +480,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
   const int nseg_gran = (s1 - s0 + G::NTG - 1) / G::NTG;
   const int tfirst = OUTPUT ? s0 : s0 + (nseg_gran - 1) * G::NTG;
   const int tstep = OUTPUT ? G::NTG : -G::NTG;
-  if (s0 < s1) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, tfirst, s1, tl0, coff, a.W);
+  if (s0 < s1) KK::fetch(raw, srcK, srcG, srcV, tfirst, tl0, coff, a.W);
   __syncthreads();  // conv weights are in LDS
 
   // Per granule: compute stage, barrier, MFMA stage, barrier.
@@ -518,7 +511,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
       __syncthreads();
       {
         // next granule's rows travel while the matrix cores work
-        if (gi + 1 < nseg_gran) KK::template fetch<0>(raw, srcK, srcG, srcV, srcQ, t0 + tstep, s1, tl0, coff, a.W);
+        if (gi + 1 < nseg_gran) KK::fetch(raw, srcK, srcG, srcV, t0 + tstep, tl0, coff, a.W);
 
         // =========================== MFMA stage: 16 tokens at a time ===========================
 #pragma unroll 1
