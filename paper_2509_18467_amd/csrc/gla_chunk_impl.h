@@ -177,7 +177,7 @@ struct Kernel {
 
   // ---- HBM -> registers: the raw rows of the granule starting at token t0
   // Gate logits, keys and values are issued one stage ahead (under the MFMA stage); the query heads are fetched
-  // inside the compute stage, one head ahead of their use (fetch_head).  Prefetching query heads a stage ahead
+  // inside the compute stage, two heads ahead of their use (fetch_head).  Prefetching query heads a stage ahead
   // as well measured slower at every count tried (larger bursts into the memory pipeline, more registers live
   // across the MFMA stage).
   __device__ static inline void fetch(Raw<NQ>& raw, const RowSrc& srcK, const RowSrc& srcG, const RowSrc& srcV,
@@ -200,8 +200,9 @@ struct Kernel {
                                         const float* wl, int t0, int s1, int tl0, int c0, int mcw, int th,
                                         float gate_scale) {
     const int tok0 = t0 + tl0;
-    // query heads are fetched one head ahead of their use
+    // query heads are fetched two heads ahead of their use
     if (OUTPUT) fetch_head(raw, srcQ, 0, t0, tl0, coff, W);
+    if (OUTPUT && NQ > 1) fetch_head(raw, srcQ, 1, t0, tl0, coff, W);
     // keys first: conv + phi into kf, which the gate loop below scales in place by 1/E as it goes
     float kf[8][2];
     conv_phi<MODE>(raw.k, wl + ((size_t)GR * D + c0) * 4, kf);
@@ -283,7 +284,7 @@ struct Kernel {
 #pragma unroll
       for (int hh = 0; hh < NQ; ++hh) {
         __builtin_amdgcn_sched_barrier(0);
-        if (hh + 1 < NQ) fetch_head(raw, srcQ, hh + 1, t0, tl0, coff, W);
+        if (hh + 2 < NQ) fetch_head(raw, srcQ, hh + 2, t0, tl0, coff, W);
         float qf[8][2];
         conv_phi<MODE>(raw.q[hh], wl + ((size_t)hh * D + c0) * 4, qf);
         unsigned char* qp = smem + G::kQp + (hh * G::NTG + tl0) * G::QRS + c0 * 2;
