@@ -38,9 +38,10 @@ inline size_t elem_bytes(const lawcat_desc* d) { return d->dtype == LAWCAT_DTYPE
 // Which prefill implementation a desc selects.
 enum class Path { kRecurrentF32, kChunkBf16 };
 inline Path prefill_path(const lawcat_desc* d) {
-  // the chunk kernels address one batch element's rows with 32-bit byte offsets (buffer loads); offsets of
-  // the three rows before the first token wrap around and must still land past the end of the buffer
-  const bool rows_fit = ((uint64_t)d->T + 4) * d->Hq * d->dk * 2 < (1ull << 32);
+  // the chunk kernels address one batch element's rows with 32-bit byte offsets (buffer loads): offsets of the
+  // three rows before the first token wrap around and must still land past the end of the buffer, and the rows
+  // of the last granule past T (fewer than 64) must not wrap at all, so that they read as zero
+  const bool rows_fit = ((uint64_t)d->T + 128) * d->Hq * d->dk * 2 < (1ull << 32);
   // one workgroup row per (batch, kv head) on the grid's y axis
   const bool heads_fit = (uint64_t)d->B * d->Hkv <= 65535;
   return (d->dtype == LAWCAT_DTYPE_BF16 && chunk_path_supports(d->Hq / d->Hkv) && rows_fit && heads_fit)

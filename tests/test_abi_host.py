@@ -97,6 +97,11 @@ def test_path_selection_shows_in_workspace_size():
     assert 0 < lawcat.workspace_bytes(ok, call) < 32 * 1024 * 1024  # segment states only
     long_rows = lawcat.make_desc(1, 1 << 20, 32, 8, 64)             # 2^20 tokens x 4 KiB rows = 4 GiB
     assert lawcat.workspace_bytes(long_rows, call) == unfused(1, 1 << 20, 32, 8, 64)
+    # the last granule's rows past T must not wrap a 32-bit offset either: the limit sits 128 rows below 4 GiB
+    near = lawcat.make_desc(1, (1 << 20) - 64, 32, 8, 64)
+    assert lawcat.workspace_bytes(near, call) == unfused(1, (1 << 20) - 64, 32, 8, 64)
+    below = lawcat.make_desc(1, (1 << 20) - 129, 32, 8, 64)
+    assert 0 < lawcat.workspace_bytes(below, call) < 64 * 1024 * 1024
     many_heads = lawcat.make_desc(70000, 16, 1, 1, 64)
     assert lawcat.workspace_bytes(many_heads, call) == unfused(70000, 16, 1, 1, 64)
     group8 = lawcat.make_desc(1, 4096, 16, 2, 64)   # covered by two launches over 4 query heads each
