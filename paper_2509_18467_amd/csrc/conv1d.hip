@@ -9,7 +9,7 @@
 namespace lawcat {
 namespace {
 
-constexpr int kStrip = 32;  // tokens per thread
+constexpr int kStrip = 64;  // tokens per thread
 constexpr int kGroup = 4;   // rows fetched together, one group ahead of the arithmetic
 
 template <typename T> struct Io;
@@ -84,10 +84,27 @@ __global__ void __launch_bounds__(256) conv1d_causal_kernel(const T* __restrict_
   const int e0 = col * VEC;  // first element (h*d + c) of this thread's column group
 
   float wt[4][VEC];  // wt[delta][i]
+  if (W == 4) {
+    // the VEC x 4 taps of this column group are contiguous: four whole-vector loads instead of 4 VEC scalar
+    // ones (the scalar form made every thread start with a long chain of small dependent loads)
+    float flat[4 * VEC];
 #pragma unroll
-  for (int i = 0; i < VEC; ++i)
+    for (int j = 0; j < 4; ++j) {
+      float part[VEC];
+      Io<T>::load(w + (size_t)e0 * 4 + j * VEC, part);
 #pragma unroll
-    for (int dl = 0; dl < 4; ++dl) wt[dl][i] = dl < W ? Io<T>::scalar(w + (size_t)(e0 + i) * W + dl) : 0.f;
+      for (int i = 0; i < VEC; ++i) flat[j * VEC + i] = part[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; ++i)
+#pragma unroll
+      for (int dl = 0; dl < 4; ++dl) wt[dl][i] = flat[i * 4 + dl];
+  } else {
+#pragma unroll
+    for (int i = 0; i < VEC; ++i)
+#pragma unroll
+      for (int dl = 0; dl < 4; ++dl) wt[dl][i] = dl < W ? Io<T>::scalar(w + (size_t)(e0 + i) * W + dl) : 0.f;
+  }
 
   const int t0 = s * kStrip;
   float win[3][VEC];  // win[j] = row t-1-j

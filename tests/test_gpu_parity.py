@@ -30,6 +30,7 @@ def _store(wl, a):
 @pytest.mark.parametrize("T,Hh,d,W,phi,halo", [
     (256, 2, 64, 4, 0, False), (37, 3, 64, 4, 1, True), (1, 8, 128, 4, 1, True), (2, 8, 128, 4, 0, True),
     (1000, 4, 128, 2, 1, False), (129, 2, 64, 1, 1, False), (530, 32, 64, 3, 0, True),
+    (1000, 4, 64, 4, 1, True), (193, 2, 128, 4, 0, False),
 ])
 def test_conv1d_causal(oracle, dtype, T, Hh, d, W, phi, halo):
     wl = Workload("conv", 2, T, Hh, Hh, d, W, dtype)
