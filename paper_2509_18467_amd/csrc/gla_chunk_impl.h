@@ -91,6 +91,11 @@ __device__ inline uint32_t pack2(float a, float b) {
   bf16x2 v = {(__bf16)a, (__bf16)b};  // v_cvt_pk_bf16_f32, round to nearest even
   return __builtin_bit_cast(uint32_t, v);
 }
+// value of the lane whose byte index (lane * 4) is given; callers form the index once, not per exchange (the
+// generic shuffle recomputes it with half a dozen instructions every time)
+__device__ inline float lane_get(int byte_index, float v) {
+  return __int_as_float(__builtin_amdgcn_ds_bpermute(byte_index, __float_as_int(v)));
+}
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ inline float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ inline float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
@@ -200,6 +205,7 @@ struct Kernel {
                                         const float* wl, int t0, int s1, int tl0, int c0, int mcw, int th,
                                         float gate_scale) {
     const int tok0 = t0 + tl0;
+    const int idx32 = (int)(((threadIdx.x & 63) ^ 32) << 2);  // the lane that holds the other half of the chunk
     // query heads are fetched two heads ahead of their use
     if (OUTPUT) fetch_head(raw, srcQ, 0, t0, tl0, coff, W);
     if (OUTPUT && NQ > 1) fetch_head(raw, srcQ, 1, t0, tl0, coff, W);
@@ -234,8 +240,8 @@ struct Kernel {
     float pre[2], ipre[2], btot[2];
 #pragma unroll
     for (int ch = 0; ch < 2; ++ch) {
-      const float ot = __shfl_xor(run[ch], 32);
-      const float oit = __shfl_xor(irun[ch], 32);
+      const float ot = lane_get(idx32, run[ch]);
+      const float oit = lane_get(idx32, irun[ch]);
       pre[ch] = th ? ot : 1.f;
       ipre[ch] = th ? oit : 1.f;
       btot[ch] = th ? ot * run[ch] : run[ch] * ot;  // first-half product times second-half product
@@ -303,6 +309,7 @@ struct Kernel {
                                               int s1, int tl0, int c0, int mcw, int th, float gate_scale,
                                               float (&rgran)[2]) {
     const int tok0 = t0 + tl0;
+    const int idx32 = (int)(((threadIdx.x & 63) ^ 32) << 2);  // the lane that holds the other half of the chunk
     float al[8][2];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -329,7 +336,7 @@ struct Kernel {
     float btot[2], tail[2];
 #pragma unroll
     for (int ch = 0; ch < 2; ++ch) {
-      const float ot = __shfl_xor(ptot[ch], 32);
+      const float ot = lane_get(idx32, ptot[ch]);
       tail[ch] = th ? 1.f : ot;               // first half of the chunk is also decayed by the second half
       btot[ch] = th ? ot * ptot[ch] : ptot[ch] * ot;
     }
@@ -568,12 +575,13 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
               const uint32_t pl1 = pack2(pt[2] - bf_lo(ph1), pt[3] - bf_hi(ph1));
               unsigned char* ps = smem + G::kPs + ((mc & 1) * GR + myh) * 1024 + l * 16;
               *reinterpret_cast<uint4*>(ps) = make_uint4(ph0, ph1, pl0, pl1);
-              // column sum over the 16 keys: 4 in this lane, the other 12 in the lanes 16, 32 and 48 away
-              float cs = (pt[0] + pt[1]) + (pt[2] + pt[3]);
-              cs += __shfl_xor(cs, 16);
-              cs += __shfl_xor(cs, 32);
+              // column sums over the 16 keys: a ones operand against the packed scores adds them to q'.z in every
+              // row of the tile (one MFMA instead of two cross-lane exchanges; it sums exactly the high parts
+              // and residuals that the value product below uses)
+              const bf16x8 ones8 = __builtin_bit_cast(bf16x8, make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u));
+              dz = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones8, __builtin_bit_cast(bf16x8, make_uint4(ph0, ph1, pl0, pl1)), dz, 0, 0, 0);
               if (g4 == 0)
-                *reinterpret_cast<float*>(smem + G::kDn + (((mc & 1) * GR + myh) * 16 + n) * 4) = dz[0] + cs + a.eps;
+                *reinterpret_cast<float*>(smem + G::kDn + (((mc & 1) * GR + myh) * 16 + n) * 4) = dz[0] + a.eps;
             }
             // [V|1]^T against (high, residual) in one k = 32 MFMA: the same four tokens fill both halves of A
             bf16x8 vv[G::CT];
