@@ -78,8 +78,11 @@ def check() -> int:
                     # the last two barriers of the granule loop: compute -> MFMA stage, and the one per chunk;
                     # the loop ends at the last backward branch to its header
                     bars = [j for j, l in enumerate(body) if "s_barrier" in l]
-                    waits = [(j, body[j].strip()) for j in range(bars[-2], _loop_end(body, bars[-2]))
-                             if "s_waitcnt" in body[j] and "vmcnt" in body[j]]
+                    if len(bars) >= 2:
+                        waits = [(j, body[j].strip()) for j in range(bars[-2], _loop_end(body, bars[-2]))
+                                 if "s_waitcnt" in body[j] and "vmcnt" in body[j]]
+                    else:
+                        waits = [(0, "(fewer than two barriers found: kernel layout not recognised)")]
                 flag = ""
                 if r.get("scratch", 0) > 0:
                     flag += "  <-- spills"
