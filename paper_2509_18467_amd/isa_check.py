@@ -75,14 +75,18 @@ def check() -> int:
                 r = res.get(name, {})
                 waits = []
                 if output:
-                    # the last two barriers of the granule loop: compute -> MFMA stage, and the one per chunk;
-                    # the loop ends at the last backward branch to its header
+                    # inside the granule loop the barriers cut the code into regions; those that hold MFMAs make
+                    # up the MFMA stage (the compute stage has none), whatever order the blocks were laid out in
                     bars = [j for j, l in enumerate(body) if "s_barrier" in l]
-                    if len(bars) >= 2:
-                        waits = [(j, body[j].strip()) for j in range(bars[-2], _loop_end(body, bars[-2]))
-                                 if "s_waitcnt" in body[j] and "vmcnt" in body[j]]
+                    if bars:
+                        end = _loop_end(body, bars[-1])
+                        cuts = [j for j in bars if j < end] + [end]
+                        for lo, hi in zip(cuts[:-1], cuts[1:]):
+                            if any("v_mfma" in body[j] for j in range(lo, hi)):
+                                waits += [(j, body[j].strip()) for j in range(lo, hi)
+                                          if "s_waitcnt" in body[j] and "vmcnt" in body[j]]
                     else:
-                        waits = [(0, "(fewer than two barriers found: kernel layout not recognised)")]
+                        waits = [(0, "(no barrier found: kernel layout not recognised)")]
                 flag = ""
                 if r.get("scratch", 0) > 0:
                     flag += "  <-- spills"
