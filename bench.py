@@ -31,7 +31,7 @@ def algorithmic_bytes_per_token(wl) -> int:
 
 
 class HipEvents:
-    """Raw hipEvent_t pairs (ctypes on libamdhip64) for the library's output-pass trace hook."""
+    """Raw hipEvent_t pairs (ctypes on libamdhip64) for lawcat_layer_prefill_timed."""
 
     def __init__(self, n):
         self.hip = ctypes.CDLL("libamdhip64.so")
@@ -85,10 +85,14 @@ def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0, segment=0
         sets.append(d)
     ws = lawcat.alloc_workspace(desc, lawcat.CALL_LAYER_PREFILL)
 
-    def step(i):
+    def step(i, ev=None):
         d = sets[i % nsets]
-        lawcat.layer_prefill(desc, d["Q"], d["K"], d["V"], d["G"], d["wq"], d["wk"], None, None, None, None,
-                             d["O"], None, d["S"], d["z"], d["qt"], d["kt"], ws)
+        args = (desc, d["Q"], d["K"], d["V"], d["G"], d["wq"], d["wk"], None, None, None, None,
+                d["O"], None, d["S"], d["z"], d["qt"], d["kt"], ws)
+        if ev is None:
+            lawcat.layer_prefill(*args)
+        else:
+            lawcat.layer_prefill_timed(*args, ev[0].value, ev[1].value)
 
     for i in range(warmup):
         step(i)
@@ -96,12 +100,9 @@ def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0, segment=0
     ev = HipEvents(steps) if trace else None
     t0 = time.perf_counter()
     for i in range(steps):
-        if ev:
-            lawcat.trace_output_pass(ev.pairs[i][0].value, ev.pairs[i][1].value)
-        step(i)
+        step(i, ev.pairs[i] if ev else None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    lawcat.trace_output_pass(None, None)
     ms_step = (t1 - t0) * 1e3 / steps
     kern_ms = None
     if ev:

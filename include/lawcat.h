@@ -131,13 +131,20 @@ LAWCAT_API int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, cons
                          void* k_tail_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Measurement aid.  While both events (hipEvent_t passed as void*) are non-NULL, every prefill call
- * that runs the bf16 matrix-core path launches its output-pass kernel with `before` and `after` as the
- * kernel's start and stop events (they take the kernel's own begin and end timestamps on the call's
- * stream), so a caller can time that kernel alone with hipEventElapsedTime.  Pass NULLs to switch it
- * off.  Process-wide state, not thread-safe; the events stay owned by the caller.
+ * Measurement variant of lawcat_layer_prefill (same arguments, same result) for benchmarks: the dominant
+ * kernel of the bf16 matrix-core path, the output pass, is launched with `ev_start` and `ev_stop`
+ * (hipEvent_t passed as void*, both required, owned by the caller) as its start and stop events, so that
+ * hipEventElapsedTime(ev_start, ev_stop) is that kernel's duration on the call's stream.  With more than
+ * four query heads per kv head the events bracket the first output-pass launch.  Returns
+ * LAWCAT_E_UNSUPPORTED for a desc that the matrix-core path does not serve (fp32 storage).  No state is
+ * kept between calls.
  */
-LAWCAT_API void lawcat_trace_output_pass(void* before, void* after);
+LAWCAT_API int lawcat_layer_prefill_timed(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
+                               const void* gate_logits, const void* wq, const void* wk, const float* S0,
+                               const float* z0, const void* q_halo, const void* k_halo, void* O,
+                               float* den_out, float* S_out, float* z_out, void* q_tail_out,
+                               void* k_tail_out, void* workspace, size_t workspace_bytes, void* stream,
+                               void* ev_start, void* ev_stop);
 
 /* Static string for a lawcat_status value. */
 LAWCAT_API const char* lawcat_status_string(int status);

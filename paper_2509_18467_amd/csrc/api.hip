@@ -144,11 +144,15 @@ int lawcat_gla_step(const lawcat_desc* desc, const void* q, const void* k, const
   return hip_status(launch_gla_step(r, static_cast<hipStream_t>(stream)));
 }
 
-int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
-                         const void* gate_logits, const void* wq, const void* wk, const float* S0,
-                         const float* z0, const void* q_halo, const void* k_halo, void* O, float* den_out,
-                         float* S_out, float* z_out, void* q_tail_out, void* k_tail_out, void* workspace,
-                         size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+namespace {
+
+int layer_prefill_impl(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
+                       const void* gate_logits, const void* wq, const void* wk, const float* S0,
+                       const float* z0, const void* q_halo, const void* k_halo, void* O, float* den_out,
+                       float* S_out, float* z_out, void* q_tail_out, void* k_tail_out, void* workspace,
+                       size_t workspace_bytes, void* stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   int st = check_desc(desc, true);
   if (st != LAWCAT_OK) return st;
   if (!Q || !K || !V || !gate_logits || !wq || !wk || !O || !S_out || !z_out) return LAWCAT_E_NULL;
@@ -171,8 +175,10 @@ int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, 
     c.W = desc->conv_width; c.phi = desc->feature_map; c.fuse_conv = 1;
     c.gate_scale = desc->gate_scale; c.eps = desc->eps; c.plan = plan_for(desc);
     c.q_tail = q_tail_out; c.k_tail = k_tail_out;
+    c.ev_start = ev_start; c.ev_stop = ev_stop;
     return hip_status(launch_gla_chunk(c, hs));
   }
+  if (ev_start != nullptr || ev_stop != nullptr) return LAWCAT_E_UNSUPPORTED;  // only the bf16 path has the hook
 
   // Unfused path (fp32 storage): conv + phi into the workspace, then the fp32 recurrence.
   const size_t rows = (size_t)desc->B * desc->T;
@@ -196,8 +202,28 @@ int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, 
   return hip_status(launch_gla_recurrent(r, hs));
 }
 
-void lawcat_trace_output_pass(void* before, void* after) {
-  set_output_pass_events(static_cast<hipEvent_t>(before), static_cast<hipEvent_t>(after));
+}  // namespace
+
+extern "C" {
+
+int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
+                         const void* gate_logits, const void* wq, const void* wk, const float* S0,
+                         const float* z0, const void* q_halo, const void* k_halo, void* O, float* den_out,
+                         float* S_out, float* z_out, void* q_tail_out, void* k_tail_out, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  return layer_prefill_impl(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,
+                            q_tail_out, k_tail_out, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+int lawcat_layer_prefill_timed(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
+                               const void* gate_logits, const void* wq, const void* wk, const float* S0,
+                               const float* z0, const void* q_halo, const void* k_halo, void* O, float* den_out,
+                               float* S_out, float* z_out, void* q_tail_out, void* k_tail_out, void* workspace,
+                               size_t workspace_bytes, void* stream, void* ev_start, void* ev_stop) {
+  if (ev_start == nullptr || ev_stop == nullptr) return LAWCAT_E_NULL;
+  return layer_prefill_impl(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,
+                            q_tail_out, k_tail_out, workspace, workspace_bytes, stream,
+                            static_cast<hipEvent_t>(ev_start), static_cast<hipEvent_t>(ev_stop));
 }
 
 const char* lawcat_status_string(int status) {

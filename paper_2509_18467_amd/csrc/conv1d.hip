@@ -208,20 +208,3 @@ hipError_t launch_conv1d(const ConvParams& p, hipStream_t stream) {
 }
 
 }  // namespace lawcat
-
-namespace lawcat {
-hipError_t launch_conv_tail(const void* x, const void* halo, void* tail_out, int B, int T, int H, int d, int W,
-                            int bf16, hipStream_t stream) {
-  if (W <= 1 || tail_out == nullptr) return hipSuccess;
-  const int rowlen = H * d;
-  const long long total = (long long)B * (W - 1) * rowlen;
-  const unsigned grid = (unsigned)((total + 255) / 256);
-  if (bf16)
-    hipLaunchKernelGGL(conv_tail_kernel<bf16_t>, dim3(grid), dim3(256), 0, stream, (const bf16_t*)x,
-                       (const bf16_t*)halo, (bf16_t*)tail_out, B, T, rowlen, W);
-  else
-    hipLaunchKernelGGL(conv_tail_kernel<float>, dim3(grid), dim3(256), 0, stream, (const float*)x,
-                       (const float*)halo, (float*)tail_out, B, T, rowlen, W);
-  return hipGetLastError();
-}
-}  // namespace lawcat

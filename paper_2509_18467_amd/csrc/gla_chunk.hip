@@ -4,15 +4,9 @@
 
 namespace lawcat {
 namespace chunk {
-hipEvent_t g_ev_before = nullptr, g_ev_after = nullptr;
-hipError_t launch_d64(const ChunkArgs& a, int group, int mode, hipStream_t stream);
-hipError_t launch_d128(const ChunkArgs& a, int group, int mode, hipStream_t stream);
+hipError_t launch_d64(const ChunkArgs& a, int group, int mode, hipStream_t stream, const TraceEvents& ev);
+hipError_t launch_d128(const ChunkArgs& a, int group, int mode, hipStream_t stream, const TraceEvents& ev);
 }  // namespace chunk
-
-void set_output_pass_events(hipEvent_t before, hipEvent_t after) {
-  chunk::g_ev_before = before;
-  chunk::g_ev_after = after;
-}
 
 bool chunk_path_supports(int group) { return group >= 1 && group <= 64; }
 
@@ -52,7 +46,8 @@ hipError_t launch_gla_chunk(const ChunkParams& p, hipStream_t stream) {
   a.gate_scale = p.gate_scale; a.eps = p.eps;
   const int group = p.Hq / p.Hkv;
   const int mode = !p.fuse_conv ? chunk::kPlain : (p.phi == 1 ? chunk::kConvElu : chunk::kConvId);
-  return p.d == 64 ? chunk::launch_d64(a, group, mode, stream) : chunk::launch_d128(a, group, mode, stream);
+  const chunk::TraceEvents ev{p.ev_start, p.ev_stop};
+  return p.d == 64 ? chunk::launch_d64(a, group, mode, stream, ev) : chunk::launch_d128(a, group, mode, stream, ev);
 }
 
 }  // namespace lawcat

@@ -23,6 +23,9 @@
 // Per-step decay is floored at 2^-7.5 so that a chunk's 1/E stays below 2^120.
 #pragma once
 #include <hip/hip_ext.h>
+
+#include <mutex>
+
 #include "kernels.h"
 
 namespace lawcat {
@@ -43,6 +46,11 @@ constexpr int kChunk = 16;
 constexpr int kPlain = 0;     // q, k are already q-dot, k-dot (lawcat_gla_prefill)
 constexpr int kConvId = 1;    // conv, identity feature map
 constexpr int kConvElu = 2;   // conv, 1 + ELU
+
+// Optional start/stop events of the output-pass kernel (measurement entry point only).
+struct TraceEvents {
+  hipEvent_t start, stop;
+};
 
 struct ChunkArgs {
   const bf16_t *q, *k, *v, *g, *wq, *wk, *q_halo, *k_halo;
@@ -799,15 +807,26 @@ __global__ void __launch_bounds__(256) segment_scan_kernel(float* __restrict__ w
   if (live && se == last && sb < se) slot[(size_t)last * kSlot + e] = st;
 }
 
-template <typename K>
-hipError_t set_lds(K kernel, int bytes) {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+// Raises the kernel's dynamic LDS limit once per device (the attribute is per device and per process); safe to
+// call from several host threads.  The kernel is a template argument so that every kernel has its own flags.
+template <auto kernel>
+hipError_t set_lds(int bytes) {
+  constexpr int kMaxDev = 64;
+  static std::once_flag once[kMaxDev];
+  static hipError_t result[kMaxDev];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  auto set = [&] {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  };
+  if (dev < 0 || dev >= kMaxDev) return set();
+  std::call_once(once[dev], [&] { result[dev] = set(); });
+  return result[dev];
 }
 
-extern hipEvent_t g_ev_before, g_ev_after;
-
 template <int D, int GR, int MODE>
-hipError_t launch_all(const ChunkArgs& a, hipStream_t stream, bool with_state_pass) {
+hipError_t launch_all(const ChunkArgs& a, hipStream_t stream, bool with_state_pass, const TraceEvents& ev) {
   using G = Geo<D, GR>;
   const int heads = a.B * a.Hkv;
   hipError_t e;
@@ -815,12 +834,8 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream, bool with_state_pa
     // GR = 0: key side only
     auto k1 = gla_chunk_kernel<D, 0, MODE, false>;
     constexpr int lds1 = Geo<D, 0>::kBytes;
-    static bool set1 = false;
-    if (!set1) {
-      e = set_lds(k1, lds1);
-      if (e != hipSuccess) return e;
-      set1 = true;
-    }
+    e = set_lds<gla_chunk_kernel<D, 0, MODE, false>>(lds1);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k1, dim3(a.nseg - 1, heads), dim3(G::TEAM), lds1, stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -830,15 +845,11 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream, bool with_state_pa
     if (e != hipSuccess) return e;
   }
   auto k3 = gla_chunk_kernel<D, GR, MODE, true>;
-  static bool set3 = false;
-  if (!set3) {
-    e = set_lds(k3, G::kBytes);
-    if (e != hipSuccess) return e;
-    set3 = true;
-  }
-  // measurement hook: the two events take the kernel's own start and stop timestamps (no dispatch gaps)
-  if (g_ev_before != nullptr && g_ev_after != nullptr)
-    hipExtLaunchKernelGGL(k3, dim3(a.nseg, heads), dim3(G::TEAM), G::kBytes, stream, g_ev_before, g_ev_after, 0, a);
+  e = set_lds<gla_chunk_kernel<D, GR, MODE, true>>(G::kBytes);
+  if (e != hipSuccess) return e;
+  // measurement entry point: the two events take the kernel's own start and stop timestamps (no dispatch gaps)
+  if (ev.start != nullptr && ev.stop != nullptr)
+    hipExtLaunchKernelGGL(k3, dim3(a.nseg, heads), dim3(G::TEAM), G::kBytes, stream, ev.start, ev.stop, 0, a);
   else
     hipLaunchKernelGGL(k3, dim3(a.nseg, heads), dim3(G::TEAM), G::kBytes, stream, a);
   return hipGetLastError();
@@ -848,19 +859,20 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream, bool with_state_pa
 // share one state pass and one scan (the key side does not depend on the query heads), and each writes the
 // same final state.
 template <int D>
-hipError_t launch_d(const ChunkArgs& a0, int group, int mode, hipStream_t stream) {
+hipError_t launch_d(const ChunkArgs& a0, int group, int mode, hipStream_t stream, const TraceEvents& ev0) {
   ChunkArgs a = a0;
   a.group = group;
   bool first = true;
   for (int qh0 = 0; qh0 < group;) {
     const int left = group - qh0, gr = left >= 4 ? 4 : (left >= 2 ? 2 : 1);
     a.qh0 = qh0;
+    const TraceEvents ev = first ? ev0 : TraceEvents{nullptr, nullptr};
     hipError_t e;
 #define LAWCAT_CASE(GRV)                                                                      \
   case GRV:                                                                                   \
-    e = mode == kPlain    ? launch_all<D, GRV, kPlain>(a, stream, first)                      \
-        : mode == kConvId ? launch_all<D, GRV, kConvId>(a, stream, first)                     \
-                          : launch_all<D, GRV, kConvElu>(a, stream, first);                   \
+    e = mode == kPlain    ? launch_all<D, GRV, kPlain>(a, stream, first, ev)                  \
+        : mode == kConvId ? launch_all<D, GRV, kConvId>(a, stream, first, ev)                 \
+                          : launch_all<D, GRV, kConvElu>(a, stream, first, ev);               \
     break;
     switch (gr) {
       LAWCAT_CASE(1)

@@ -41,10 +41,6 @@ hipError_t launch_gla_recurrent(const RecurrentParams& p, hipStream_t stream);
 // One token per sequence, S_out/z_out updated in place (S0, z0, den_out, T are not read).
 hipError_t launch_gla_step(const RecurrentParams& p, hipStream_t stream);
 
-// Copies the last W-1 raw rows of [halo ; x] (the conv cache) without running the conv.
-hipError_t launch_conv_tail(const void* x, const void* halo, void* tail_out, int B, int T, int H, int d, int W,
-                            int bf16, hipStream_t stream);
-
 // How the bf16 matrix-core prefill splits a sequence: `nseg` segments of `seg_len` tokens per
 // (batch, kv head), each carried sequentially by one workgroup.  With nseg > 1 a first pass
 // computes every segment's state contribution and a scan turns them into start states.
@@ -79,9 +75,10 @@ struct ChunkParams {
   int fuse_conv;
   float gate_scale, eps;
   ChunkPlan plan;
+  // measurement only: when both are set, the (first) output-pass kernel is launched with them as its start and
+  // stop events
+  hipEvent_t ev_start, ev_stop;
 };
 hipError_t launch_gla_chunk(const ChunkParams& p, hipStream_t stream);
-// Events recorded around the output-pass kernel of launch_gla_chunk (nullptr = off).
-void set_output_pass_events(hipEvent_t before, hipEvent_t after);
 
 }  // namespace lawcat

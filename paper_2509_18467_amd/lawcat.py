@@ -21,7 +21,7 @@ CALL_CONV1D, CALL_GLA_PREFILL, CALL_GLA_STEP, CALL_LAYER_PREFILL = 0, 1, 2, 3
 
 EXPORTS = (
     "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gla_prefill", "lawcat_gla_step",
-    "lawcat_layer_prefill", "lawcat_trace_output_pass", "lawcat_status_string", "lawcat_version",
+    "lawcat_layer_prefill", "lawcat_layer_prefill_timed", "lawcat_status_string", "lawcat_version",
 )
 
 
@@ -70,8 +70,8 @@ def lib() -> ctypes.CDLL:
         L.lawcat_status_string.argtypes = [ci]
         L.lawcat_status_string.restype = ctypes.c_char_p
         L.lawcat_version.restype = ci
-        L.lawcat_trace_output_pass.argtypes = [vp, vp]
-        L.lawcat_trace_output_pass.restype = None
+        L.lawcat_layer_prefill_timed.argtypes = [dp] + [vp] * 17 + [sz, vp, vp, vp]
+        L.lawcat_layer_prefill_timed.restype = ci
         _lib = L
     return _lib
 
@@ -82,11 +82,6 @@ def status_string(status: int) -> str:
 
 def version() -> int:
     return int(lib().lawcat_version())
-
-
-def trace_output_pass(before, after):
-    """before/after: raw hipEvent_t handles (ints) or None to switch tracing off."""
-    lib().lawcat_trace_output_pass(ctypes.c_void_p(before), ctypes.c_void_p(after))
 
 
 def make_desc(B, T, Hq, Hkv, d, *, conv_width=4, dtype=DTYPE_BF16, feature_map=PHI_ELU1, chunk=0,
@@ -138,6 +133,17 @@ def layer_prefill(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O,
                                       _p(S0), _p(z0), _p(q_halo), _p(k_halo), _p(O), _p(den_out), _p(S_out),
                                       _p(z_out), _p(q_tail_out), _p(k_tail_out), _p(workspace), nbytes,
                                       _stream(stream)))
+
+
+def layer_prefill_timed(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,
+                        q_tail_out, k_tail_out, workspace, ev_start, ev_stop, stream=None):
+    """ev_start/ev_stop: raw hipEvent_t handles (ints)."""
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lawcat_layer_prefill_timed(ctypes.byref(desc), _p(Q), _p(K), _p(V), _p(gate_logits), _p(wq),
+                                            _p(wk), _p(S0), _p(z0), _p(q_halo), _p(k_halo), _p(O), _p(den_out),
+                                            _p(S_out), _p(z_out), _p(q_tail_out), _p(k_tail_out), _p(workspace),
+                                            nbytes, _stream(stream), ctypes.c_void_p(ev_start),
+                                            ctypes.c_void_p(ev_stop)))
 
 
 def alloc_workspace(desc, which_call, device="cuda"):
