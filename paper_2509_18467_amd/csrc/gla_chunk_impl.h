@@ -4,10 +4,14 @@
 //
 // Algebra.  Split the sum over i in the state/output equations of section 4.2 at the start
 // of a 16-token chunk.  With E_t = prod of alpha over the chunk's tokens up to t (per key
-// channel) the output of token t in the chunk is
-//   num_t = (q_t (.) E_t) S_start + sum_{i<=t} [(q_t (.) E_t) . (k_i / E_i)] v_i
-//   den_t = (q_t (.) E_t) z_start + sum_{i<=t} [(q_t (.) E_t) . (k_i / E_i)]
+// channel) and a per-channel reference rho the output of token t in the chunk is
+//   num_t = (q_t (.) E_t/rho) (rho (.) S_start) + sum_{i<=t} [(q_t (.) E_t/rho) . (k_i rho/E_i)] v_i
+//   den_t = (q_t (.) E_t/rho) (rho (.) z_start) + sum_{i<=t} [(q_t (.) E_t/rho) . (k_i rho/E_i)]
 // and the state after the chunk is S_end = diag(E_last) S_start + sum_i (k_i E_last/E_i)^T v_i.
+// rho is 1 for a channel whose decay over the whole chunk stays above 2^-100 (then 1/E_i cannot overflow), and
+// otherwise the decay up to the middle of the chunk (E of its eighth token), so that neither E_t/rho nor
+// rho/E_i spans more than eight steps of decay.  A chunk in which every channel has rho = 1 (the usual case)
+// skips the scaling of the state operand.
 // All the products are bf16 MFMAs with fp32 accumulation.  The normalizer z is carried as one more
 // (replicated) column tile of the state, updated by the same MFMAs against an all-ones value operand;
 // den_t is computed once per query head, by the wave that computes that head's scores, and shared
@@ -20,7 +24,8 @@
 // decay, a small scan turns them into segment start states, and the output pass starts from
 // those.
 //
-// Per-step decay is floored at 2^-7.5 so that a chunk's 1/E stays below 2^120.
+// Per-step decay is floored at 2^-13 so that eight steps of 1/alpha stay below 2^104; the floor changes
+// a state by at most 2^-13 of what the step before it held.
 #pragma once
 #include <hip/hip_ext.h>
 
@@ -38,8 +43,10 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kAlphaMin = 0.005524271728019903f;   // 2^-7.5
-constexpr float kInvAlphaMax = 181.01933598375618f;  // 2^7.5
+constexpr float kAlphaMin = 1.220703125e-4f;   // 2^-13
+constexpr float kInvAlphaMax = 8192.f;         // 2^13
+constexpr float kLog2AlphaMin = -13.f;
+constexpr float kSafeDecay = 7.888609052210118e-31f;  // 2^-100: a chunk that decays less keeps the chunk-start reference
 constexpr int kChunk = 16;
 
 // MODE of the load stage
@@ -86,10 +93,12 @@ struct Geo {
   static constexpr int kKd = kKp + (GR > 0 ? NTG * QRS : 0);  // GR == 0: the state pass keeps no Q', K' 
   static constexpr int kVt = kKd + D * TRS;
   static constexpr int kEb = kVt + D * TRS;
-  static constexpr int kWl = kEb + MCG * D * 4;
+  static constexpr int kEf = kEb + MCG * D * 4;   // the reference rho of each chunk and channel, fp32
+  static constexpr int kWl = kEf + MCG * D * 4;
   static constexpr int kPs = kWl + (GR + 1) * D * 16;   // shared scores: [2 buffers][GR heads][64 lanes] x 16 B (4 high parts, 4 residuals)
   static constexpr int kDn = kPs + 2 * GR * 2 * 512;      // shared denominators: [2 buffers][GR heads][16 queries] fp32
-  static constexpr int kBytes = kDn + 2 * GR * 64;
+  static constexpr int kFl = kDn + 2 * GR * 64;           // per load-stage wave: 1 if one of its channels uses the mid-chunk reference
+  static constexpr int kBytes = kFl + 32;
   static constexpr int kSlot = D * D + 2 * D;  // floats per workspace slot: S | z | decay
 };
 
@@ -127,13 +136,14 @@ struct RowSrc {
   __amdgpu_buffer_rsrc_t rsrc;
   const char* halo;   // nullable: first halo row of this batch, at this head's columns
   unsigned stride;    // bytes per token row
+  unsigned width;     // bytes of a row that belong to this workgroup's heads
 };
 
 __device__ inline RowSrc make_row_src(const char* base, const char* halo, unsigned stride, int T, unsigned width) {
   // stride field 0 (raw buffer); 0x00020000 = 32-bit data format of gfx9-family descriptors.  The host has
   // checked that (T + 4) * stride fits 32 bits.
   const unsigned bytes = (unsigned)(T - 1) * stride + width;
-  return RowSrc{__builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000), halo, stride};
+  return RowSrc{__builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000), halo, stride, width};
 }
 
 // Rows t0-3 .. t0+7 (+ this thread's patch offset, folded into voff) of one tensor.  t0 is uniform.
@@ -144,10 +154,15 @@ __device__ inline void load_rows(const RowSrc& s, int t0, int tl0, int W, unsign
   for (int j = CONV ? 0 : 3; j < 11; ++j)
     raw[j] = __builtin_amdgcn_raw_buffer_load_b32(s.rsrc, (int)(voff + (unsigned)(t0 - 3 + j) * s.stride), 0, 0);
   if (CONV && t0 == 0 && s.halo != nullptr && tl0 == 0) {
-    // the rows before the first token come from the caller's halo (oldest row first, W-1 rows)
+    // the rows before the first token come from the caller's halo (oldest row first, W-1 rows), read through a
+    // descriptor of its own with 32-bit offsets (64-bit row addresses would be kept in registers across the
+    // whole granule loop for this one use)
+    const __amdgpu_buffer_rsrc_t hr =
+        __builtin_amdgcn_make_buffer_rsrc((void*)s.halo, 0, (int)((unsigned)(W - 2) * s.stride + s.width), 0x00020000);
 #pragma unroll
     for (int j = 0; j < 3; ++j)
-      if (j - 3 >= -(W - 1)) raw[j] = *reinterpret_cast<const uint32_t*>(s.halo + (size_t)(W - 4 + j) * s.stride + coff);
+      if (j - 3 >= -(W - 1))
+        raw[j] = __builtin_amdgcn_raw_buffer_load_b32(hr, (int)((unsigned)(W - 4 + j) * s.stride + coff), 0, 0);
   }
 }
 
@@ -233,7 +248,7 @@ struct Kernel {
           ia = fminf(1.f + u, kInvAlphaMax);  // 1/sigmoid(g) = 1 + exp(-g)
           al = fmaxf(fast_rcp(1.f + u), kAlphaMin);
         } else {
-          const float a2 = fmaxf(-gate_scale * fast_log2(1.f + u), -7.5f);
+          const float a2 = fmaxf(-gate_scale * fast_log2(1.f + u), kLog2AlphaMin);
           al = fast_exp2(a2);
           ia = fast_exp2(-a2);
         }
@@ -244,15 +259,38 @@ struct Kernel {
         kf[i][ch] = (EDGE && tok0 + i >= s1) ? 0.f : kf[i][ch] * irun[ch];
       }
     }
-    // the other half of the chunk lives 32 lanes away
-    float pre[2], ipre[2], btot[2];
+    // Reference rho of the in-chunk factors Q' = q E_t / rho, K' = k rho / E_i.  A lane's running products start
+    // at its own half of the chunk; the other half lives 32 lanes away, and one exchange gives both halves'
+    // totals.  Usual case (the whole chunk decays by less than 2^100): rho = 1, the second half multiplies in the
+    // first half's total.  Otherwise rho = the decay over the first half: the second half is already relative
+    // to it, and the first half needs run_t / run_7 and run_7 / run_i, with this lane's own totals.
+    float pre[2], ipre[2], kdf[2];
+    {
+      float elast[2], rho[2];
+      bool mid = false;
 #pragma unroll
-    for (int ch = 0; ch < 2; ++ch) {
-      const float ot = lane_get(idx32, run[ch]);
-      const float oit = lane_get(idx32, irun[ch]);
-      pre[ch] = th ? ot : 1.f;
-      ipre[ch] = th ? oit : 1.f;
-      btot[ch] = th ? ot * run[ch] : run[ch] * ot;  // first-half product times second-half product
+      for (int ch = 0; ch < 2; ++ch) {
+        const float ot = lane_get(idx32, run[ch]);
+        const float t0 = th ? ot : run[ch];   // decay over the first half
+        const float t1 = th ? run[ch] : ot;   // decay over the second half
+        elast[ch] = t0 * t1;
+        const bool safe = elast[ch] >= kSafeDecay;
+        pre[ch] = safe ? (th ? t0 : 1.f) : (th ? 1.f : irun[ch]);
+        ipre[ch] = safe ? (th ? fast_rcp(t0) : 1.f) : (th ? 1.f : run[ch]);
+        kdf[ch] = safe ? elast[ch] : t1;      // from the reference point on to the end of the chunk
+        rho[ch] = safe ? 1.f : t0;
+        mid |= !safe;
+      }
+      if (th == 0) {
+        float* eb = reinterpret_cast<float*>(smem + G::kEb) + mcw * D + c0;
+        *reinterpret_cast<float2*>(eb) = make_float2(kdf[0], kdf[1]);   // E_last / rho
+        float* ef = reinterpret_cast<float*>(smem + G::kEf) + mcw * D + c0;
+        *reinterpret_cast<float2*>(ef) = make_float2(rho[0], rho[1]);
+      }
+      if (OUTPUT) {
+        const bool any_mid = __builtin_amdgcn_ballot_w64(mid) != 0;
+        if ((threadIdx.x & 63) == 0) *reinterpret_cast<int*>(smem + G::kFl + (threadIdx.x >> 6) * 4) = any_mid ? 1 : 0;
+      }
     }
     __builtin_amdgcn_sched_barrier(0);  // keep the sections apart: bounds live registers
     // keys: K' = k/E (in-chunk scores) and Kdec = k E_last/E (state update)
@@ -265,7 +303,7 @@ struct Kernel {
         E[i][ch] *= pre[ch];
         const float kprime = kf[i][ch] * ipre[ch];
         kf[i][ch] = kprime;
-        kdv[i][ch] = kprime * btot[ch];
+        kdv[i][ch] = kprime * kdf[ch];
       }
       if (OUTPUT) *reinterpret_cast<uint32_t*>(kp + i * G::QRS) = pack2(kf[i][0], kf[i][1]);
     }
@@ -275,10 +313,6 @@ struct Kernel {
     *reinterpret_cast<uint2*>(kdp + 8) = make_uint2(pack2(kdv[4][0], kdv[5][0]), pack2(kdv[6][0], kdv[7][0]));
     *reinterpret_cast<uint2*>(kdp + G::TRS) = make_uint2(pack2(kdv[0][1], kdv[1][1]), pack2(kdv[2][1], kdv[3][1]));
     *reinterpret_cast<uint2*>(kdp + G::TRS + 8) = make_uint2(pack2(kdv[4][1], kdv[5][1]), pack2(kdv[6][1], kdv[7][1]));
-    if (th == 0) {
-      float* eb = reinterpret_cast<float*>(smem + G::kEb) + mcw * D + c0;
-      *reinterpret_cast<float2*>(eb) = make_float2(btot[0], btot[1]);
-    }
     __builtin_amdgcn_sched_barrier(0);
     // values, transposed to channel-major (rows past the end were fetched as zero)
     uint32_t v0[4], v1[4];
@@ -327,7 +361,7 @@ struct Kernel {
         const float u = fminf(fast_exp2(-kLog2e * gl), 1e30f);  // exp(-g)
         float a1;
         if (GS1) a1 = fmaxf(fast_rcp(1.f + u), kAlphaMin);
-        else a1 = fast_exp2(fmaxf(-gate_scale * fast_log2(1.f + u), -7.5f));
+        else a1 = fast_exp2(fmaxf(-gate_scale * fast_log2(1.f + u), kLog2AlphaMin));
         if (EDGE && tok0 + i >= s1) a1 = 1.f;
         al[i][ch] = a1;
       }
@@ -529,11 +563,33 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
         // next granule's rows travel while the matrix cores work
         if (gi + 1 < nseg_gran) KK::fetch(raw, srcK, srcG, srcV, t0 + tstep, tl0, coff, a.W);
 
+        // chunks of this granule in which some channel uses the mid-chunk reference (bit mc)
+        int midmask = 0;
+        if (OUTPUT) {
+#pragma unroll
+          for (int j = 0; j < G::NW; ++j)
+            midmask |= *reinterpret_cast<const int*>(smem + G::kFl + j * 4) << (j / G::CH);
+          midmask = __builtin_amdgcn_readfirstlane(midmask);
+        }
         // =========================== MFMA stage: 16 tokens at a time ===========================
 #pragma unroll 1
         for (int mc = 0; mc < G::MCG; ++mc) {
           const int tq = t0 + kChunk * mc;  // first token of the chunk
           if (tq >= s1) break;
+          if (OUTPUT && ((midmask >> mc) & 1)) {
+            // Rare: some channel of this chunk uses the mid-chunk reference.  The accumulators take rho in place
+            // (rho (.) S is what the chunk's MFMAs need), and the state update below continues from there: its
+            // decay factor is E_last / rho.  Placed at the head of the loop body so that the rest of the chunk
+            // stays one scheduling block.
+#pragma unroll
+            for (int rt = 0; rt < G::RT; ++rt) {
+              const floatx4 r = *reinterpret_cast<const floatx4*>(smem + G::kEf + (mc * D + 16 * rt + 4 * g4) * 4);
+#pragma unroll
+              for (int ct = 0; ct < G::NT; ++ct)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) Sacc[rt][ct][i] *= r[i];
+            }
+          }
           // value fragments: lane (g4, n) holds V[tok 4 g4 .. +3][dv 16 tile + n]; serves as A (V^T) and as B (V)
           short4v vfrag[G::NT];
 #pragma unroll
@@ -545,8 +601,8 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
           vfrag[G::CT] = short4v{0x3F80, 0x3F80, 0x3F80, 0x3F80};  // ones: the state update of the normalizer z
 
           if (OUTPUT) {
-            // state as bf16 A-fragments: rows = value columns, k = key channels {4 g4 + i, 16 + 4 g4 + i} of each 32;
-            // tile CT is the normalizer z, the same in every row
+            // state (rho (.) S, see above) as bf16 A-fragments: rows = value columns, k = key channels
+            // {4 g4 + i, 16 + 4 g4 + i} of each 32; tile CT is the normalizer z, the same in every row
             bf16x8 sa[G::NT][G::KS];
 #pragma unroll
             for (int ct = 0; ct < G::NT; ++ct)
@@ -672,7 +728,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
               }
             }
           }
-          // ---- state update: S <- diag(E_last) S + Kdec^T [V | 1]
+          // ---- state update: S <- diag(E_last / rho) (rho S) + Kdec^T [V | 1]
 #pragma unroll
           for (int rt = 0; rt < G::RT; ++rt) {
             const uint2 kr = *reinterpret_cast<const uint2*>(smem + G::kKd + (16 * rt + n) * G::TRS +

@@ -232,6 +232,37 @@ def test_conv_halo_equals_longer_sequence(oracle):
     np.testing.assert_allclose(part, full[:, W - 1:], rtol=1e-14)
 
 
+@pytest.mark.parametrize("T", [1, 2, 3, 5])
+def test_conv_cache_tail_shorter_than_the_kernel(oracle, T):
+    """The conv cache after T tokens is the last W-1 raw rows of [halo ; x], also when T < W-1 (the decode
+    case: some cached rows survive).  Written out by hand for W = 4: rows are labelled by a number, so the
+    expected cache is known without any code."""
+    W, H, d = 4, 2, 3
+    halo = np.zeros((1, W - 1, H, d))
+    for r in range(W - 1):
+        halo[0, r] = -(W - 1) + r          # rows -3, -2, -1 (oldest first)
+    x = np.zeros((1, T, H, d))
+    for t in range(T):
+        x[0, t] = t                        # rows 0 .. T-1
+    expect_rows = {1: [-2, -1, 0], 2: [-1, 0, 1], 3: [0, 1, 2], 5: [2, 3, 4]}[T]
+    tail = oracle._tail(x, halo, W)
+    assert tail.shape == (1, W - 1, H, d)
+    for r, val in enumerate(expect_rows):
+        assert np.all(tail[0, r] == val)
+    # without a halo the rows before the first token are zeros
+    zero_rows = {1: [0, 0, 0], 2: [0, 0, 1], 3: [0, 1, 2], 5: [2, 3, 4]}[T]
+    tail0 = oracle._tail(x + 0.0, None, W)
+    for r, val in enumerate(zero_rows):
+        assert np.all(tail0[0, r] == val)
+    # and the cache is exactly what a continuation needs: conv over [x ; y] == conv over y with the tail as halo
+    rng = np.random.default_rng(T)
+    xr, y, w = _rand(rng, 1, T, H, d), _rand(rng, 1, 4, H, d), _rand(rng, H, d, W)
+    hr = _rand(rng, 1, W - 1, H, d)
+    whole = oracle.conv1d_causal(np.concatenate([xr, y], axis=1), w, hr)
+    cont = oracle.conv1d_causal(y, w, oracle._tail(xr, hr, W))
+    np.testing.assert_allclose(cont, whole[:, T:], rtol=0, atol=1e-14)
+
+
 def test_feature_map_one_plus_elu(oracle):
     x = np.array([-3.0, -0.5, 0.0, 0.5, 2.0]).reshape(1, 5, 1, 1)
     w = np.zeros((1, 1, 4))
