@@ -53,7 +53,8 @@ typedef enum lawcat_status {
   LAWCAT_E_UNSUPPORTED = -3, /* head dim, conv width, chunk or mode outside what the kernels cover */
   LAWCAT_E_WORKSPACE = -4,   /* workspace NULL or smaller than lawcat_workspace_bytes */
   LAWCAT_E_ALIGN = -5,       /* a pointer is not 16-byte aligned */
-  LAWCAT_E_HIP = -6          /* the HIP runtime reported a launch error */
+  LAWCAT_E_HIP = -6,         /* the HIP runtime reported a launch error */
+  LAWCAT_E_STATIC_LIMIT = -7 /* lawcat_layer_prefill_static: the call needs more than LAWCAT_STATIC_WORKSPACE_BYTES */
 } lawcat_status;
 
 enum { LAWCAT_DTYPE_F32 = 0, LAWCAT_DTYPE_BF16 = 1 };
@@ -129,6 +130,26 @@ LAWCAT_API int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, cons
                          const float* z0, const void* q_halo, const void* k_halo, void* O,
                          float* den_out, float* S_out, float* z_out, void* q_tail_out,
                          void* k_tail_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * lawcat_layer_prefill for callers that cannot allocate device memory or hold a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and same results as
+ * lawcat_layer_prefill, without `workspace`: the scratch is a buffer of LAWCAT_STATIC_WORKSPACE_BYTES that
+ * lives inside the library, one copy per GPU that loads it, until the process ends.  The call allocates and
+ * frees nothing.  A desc whose lawcat_workspace_bytes(desc, LAWCAT_CALL_LAYER_PREFILL) exceeds the buffer
+ * returns LAWCAT_E_STATIC_LIMIT before anything is enqueued (24 MiB covers the two-level carry of every
+ * single-sequence shape with up to 8 kv heads of dimension 128; fp32 storage stages q-dot and k-dot there and
+ * fits only short sequences).  Every call on a GPU uses that GPU's one buffer: calls that overlap in time on
+ * the same GPU (different streams, or several host threads) race and must be serialized by the caller.  The
+ * buffer keeps the previous call's contents; nothing in it needs to start at zero.  The first call on a
+ * device looks the buffer's address up (hipGetSymbolAddress) and should be made outside stream capture.
+ */
+#define LAWCAT_STATIC_WORKSPACE_BYTES (24u << 20)
+LAWCAT_API int lawcat_layer_prefill_static(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
+                                const void* gate_logits, const void* wq, const void* wk, const float* S0,
+                                const float* z0, const void* q_halo, const void* k_halo, void* O,
+                                float* den_out, float* S_out, float* z_out, void* q_tail_out,
+                                void* k_tail_out, void* stream);
 
 /*
  * Measurement variant of lawcat_layer_prefill (same arguments, same result) for benchmarks: the dominant

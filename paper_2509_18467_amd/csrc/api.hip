@@ -4,12 +4,37 @@
 #include "../../include/lawcat.h"
 
 #include <cmath>
+#include <mutex>
 
 #include "kernels.h"
 
 using namespace lawcat;
 
 namespace {
+
+// Scratch of lawcat_layer_prefill_static: one copy per GPU that loads the library, kept until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels receive the device address
+// that static_scratch() looks up once per device.
+__device__ __align__(256) unsigned char scratch[LAWCAT_STATIC_WORKSPACE_BYTES];
+
+hipError_t static_scratch(void** out) {
+  constexpr int kMaxDev = 64;
+  static std::once_flag once[kMaxDev];
+  static hipError_t err[kMaxDev];
+  static void* ptr[kMaxDev];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDev) return hipErrorInvalidDevice;
+  std::call_once(once[dev], [&] {
+    void* p = nullptr;
+    err[dev] = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));  // the current device's copy
+    ptr[dev] = p;
+  });
+  if (err[dev] != hipSuccess) return err[dev];
+  *out = ptr[dev];
+  return hipSuccess;
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align_up(size_t n, size_t a) { return (n + a - 1) / a * a; }
@@ -215,6 +240,21 @@ int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, 
                             q_tail_out, k_tail_out, workspace, workspace_bytes, stream, nullptr, nullptr);
 }
 
+int lawcat_layer_prefill_static(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
+                                const void* gate_logits, const void* wq, const void* wk, const float* S0,
+                                const float* z0, const void* q_halo, const void* k_halo, void* O, float* den_out,
+                                float* S_out, float* z_out, void* q_tail_out, void* k_tail_out, void* stream) {
+  const int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (workspace_bytes_checked(desc, LAWCAT_CALL_LAYER_PREFILL) > (size_t)LAWCAT_STATIC_WORKSPACE_BYTES)
+    return LAWCAT_E_STATIC_LIMIT;
+  if (!Q || !K || !V || !gate_logits || !wq || !wk || !O || !S_out || !z_out) return LAWCAT_E_NULL;
+  void* ws = nullptr;
+  if (static_scratch(&ws) != hipSuccess) return LAWCAT_E_HIP;
+  return layer_prefill_impl(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,
+                            q_tail_out, k_tail_out, ws, LAWCAT_STATIC_WORKSPACE_BYTES, stream, nullptr, nullptr);
+}
+
 int lawcat_layer_prefill_timed(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
                                const void* gate_logits, const void* wq, const void* wk, const float* S0,
                                const float* z0, const void* q_halo, const void* k_halo, void* O, float* den_out,
@@ -235,6 +275,7 @@ const char* lawcat_status_string(int status) {
     case LAWCAT_E_WORKSPACE: return "workspace missing or too small";
     case LAWCAT_E_ALIGN: return "pointer not 16-byte aligned";
     case LAWCAT_E_HIP: return "HIP launch error";
+    case LAWCAT_E_STATIC_LIMIT: return "call needs more scratch than the library's static buffer holds";
     default: return "unknown status";
   }
 }

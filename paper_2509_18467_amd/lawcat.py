@@ -21,7 +21,7 @@ CALL_CONV1D, CALL_GLA_PREFILL, CALL_GLA_STEP, CALL_LAYER_PREFILL = 0, 1, 2, 3
 
 EXPORTS = (
     "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gla_prefill", "lawcat_gla_step",
-    "lawcat_layer_prefill", "lawcat_layer_prefill_timed", "lawcat_status_string", "lawcat_version",
+    "lawcat_layer_prefill", "lawcat_layer_prefill_static", "lawcat_layer_prefill_timed", "lawcat_status_string", "lawcat_version",
 )
 
 
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.lawcat_status_string.argtypes = [ci]
         L.lawcat_status_string.restype = ctypes.c_char_p
         L.lawcat_version.restype = ci
+        L.lawcat_layer_prefill_static.argtypes = [dp] + [vp] * 16 + [vp]
+        L.lawcat_layer_prefill_static.restype = ci
         L.lawcat_layer_prefill_timed.argtypes = [dp] + [vp] * 17 + [sz, vp, vp, vp]
         L.lawcat_layer_prefill_timed.restype = ci
         _lib = L
@@ -133,6 +135,17 @@ def layer_prefill(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O,
                                       _p(S0), _p(z0), _p(q_halo), _p(k_halo), _p(O), _p(den_out), _p(S_out),
                                       _p(z_out), _p(q_tail_out), _p(k_tail_out), _p(workspace), nbytes,
                                       _stream(stream)))
+
+
+STATIC_WORKSPACE_BYTES = 24 << 20
+
+
+def layer_prefill_static(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,
+                         q_tail_out, k_tail_out, stream=None):
+    _check(lib().lawcat_layer_prefill_static(ctypes.byref(desc), _p(Q), _p(K), _p(V), _p(gate_logits), _p(wq),
+                                             _p(wk), _p(S0), _p(z0), _p(q_halo), _p(k_halo), _p(O), _p(den_out),
+                                             _p(S_out), _p(z_out), _p(q_tail_out), _p(k_tail_out),
+                                             _stream(stream)))
 
 
 def layer_prefill_timed(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,

@@ -131,3 +131,23 @@ def test_status_strings():
     assert lawcat.status_string(-99) == "unknown status"
     with pytest.raises(lawcat.LawcatError):
         lawcat._check(-3)
+
+
+def test_static_entry_point_rejects_what_its_buffer_cannot_hold():
+    """lawcat_layer_prefill_static checks the desc and the scratch need before anything else."""
+    L = lawcat.lib()
+
+    def static(desc, Q=A):
+        return L.lawcat_layer_prefill_static(ctypes.byref(desc), Q, A, A, A, A, A, None, None, None, None, A, None, A,
+                                             A, None, None, None)
+
+    big = lawcat.make_desc(4, 131072, 32, 8, 128, segment=1024)   # 32 heads x 128 segment states of 65 KiB
+    assert lawcat.workspace_bytes(big, lawcat.CALL_LAYER_PREFILL) > lawcat.STATIC_WORKSPACE_BYTES
+    assert static(big) == -7
+    fp32_long = lawcat.make_desc(1, 32768, 32, 8, 64, dtype=0)   # fp32 storage stages q-dot and k-dot: 320 MiB
+    assert static(fp32_long) == -7
+    assert static(lawcat.make_desc(1, 0, 2, 2, 64)) == -2
+    assert static(lawcat.make_desc(1, 4096, 32, 8, 64), Q=None) == -1
+    assert "static buffer" in lawcat.status_string(-7)
+    text = open(os.path.join(ROOT, "include", "lawcat.h")).read()
+    assert int(re.search(r"LAWCAT_STATIC_WORKSPACE_BYTES \((\d+)u << 20\)", text).group(1)) << 20 == lawcat.STATIC_WORKSPACE_BYTES
