@@ -558,10 +558,27 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
         else
           KK::template compute<true, false>(raw, srcQ, coff, a.W, smem, wl, t0, s1, tl0, c0, mcw, th, a.gate_scale);
       }
+      if (!OUTPUT) {
+        // State pass: everything before this granule is multiplied by rgran.  Once that is exactly zero in every
+        // channel, the operands of all remaining (earlier) granules are exactly zero and add nothing to the
+        // accumulators, so the walk can stop: same bits, fewer rows read.  (With gate logits ~ N(0,1) the decay
+        // underflows after about 150 tokens; a slowly decaying state walks its whole segment.)
+        const bool alive = __builtin_amdgcn_ballot_w64(rgran[0] != 0.f || rgran[1] != 0.f) != 0;
+        if (l == 0) *reinterpret_cast<int*>(smem + G::kFl + w * 4) = alive ? 1 : 0;
+      }
       __syncthreads();
+      bool dead = false;
+      if (!OUTPUT) {
+        int any = 0;
+#pragma unroll
+        for (int j = 0; j < G::NW; ++j) any |= *reinterpret_cast<const int*>(smem + G::kFl + j * 4);
+        dead = __builtin_amdgcn_readfirstlane(any) == 0;
+      }
+      // the waves of the chunk's latency-bound MFMA chains go ahead of a co-resident workgroup's load stage
+      if (OUTPUT && D == 64) __builtin_amdgcn_s_setprio(3);
       {
         // next granule's rows travel while the matrix cores work
-        if (gi + 1 < nseg_gran) KK::fetch(raw, srcK, srcG, srcV, t0 + tstep, tl0, coff, a.W);
+        if (gi + 1 < nseg_gran && !dead) KK::fetch(raw, srcK, srcG, srcV, t0 + tstep, tl0, coff, a.W);
 
         // chunks of this granule in which some channel uses the mid-chunk reference (bit mc)
         int midmask = 0;
@@ -748,7 +765,9 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
           }
         }
       }  // MFMA stage
+    if (OUTPUT && D == 64) __builtin_amdgcn_s_setprio(0);
     __syncthreads();
+    if (dead) break;
   }
 
   // ---- state out: first pass -> workspace slot (S | z | decay); last segment of the output pass -> S_out, z_out
