@@ -7,7 +7,11 @@ that is already resident in HBM.  Prints ONE JSON line: prefill tokens/s per lay
 HBM roofline of the dominant kernel (the output pass) timed with HIP events, and the fp64 CPU
 oracle timed on the host cores as a baseline.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--quick]
+
+A default run also reports, in the same line, the other graded shapes (T = 8K .. 128K), the identity feature
+map and a slowly decaying state at the headline shape ("sweep"), and the stand-alone conv and decode-step calls
+("side_ops").
 """
 from __future__ import annotations
 
@@ -58,7 +62,25 @@ class HipEvents:
             self.hip.hipEventDestroy(b)
 
 
-def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0, segment=0, carry=0, gate_scale=1.0):
+def device_inputs(wl, seed, dt):
+    """The synthetic layer input drawn on the GPU (same shapes and distributions as inputs.make_inputs, torch's
+    seeded generator): used where no host copy is needed, i.e. for every timing except the headline's, whose
+    first input set is also what the CPU oracle is timed on."""
+    import torch
+
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1000 + seed)
+
+    def normal(shape, scale):
+        return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * scale).to(dt)
+
+    B, T, Hq, Hkv, d, W = wl.B, wl.T, wl.Hq, wl.Hkv, wl.d, wl.W
+    return {"Q": normal((B, T, Hq, d), 0.125), "K": normal((B, T, Hkv, d), 0.125), "V": normal((B, T, Hkv, d), 0.125),
+            "G": normal((B, T, Hkv, d), 1.0), "wq": normal((Hq, d, W), W ** -0.5), "wk": normal((Hkv, d, W), W ** -0.5)}
+
+
+def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0, segment=0, carry=0, gate_scale=1.0,
+                 host_inputs=True):
     import torch
 
     from paper_2509_18467_amd import lawcat
@@ -73,10 +95,11 @@ def run_workload(wl, steps, warmup, feature_map=1, trace=True, seed=0, segment=0
     nsets = max(2, min(12, -(-(1 << 30) // bytes_step)))
     sets, host0 = [], None
     for s in range(nsets):
-        x = make_inputs(wl, seed=seed + s)
-        if s == 0:
-            host0 = x
-        d = {k: torch.from_numpy(v).to("cuda").to(dt).contiguous() for k, v in x.items()}
+        if host_inputs and s == 0:
+            host0 = make_inputs(wl, seed=seed)
+            d = {k: torch.from_numpy(v).to("cuda").to(dt).contiguous() for k, v in host0.items()}
+        else:
+            d = device_inputs(wl, seed + s, dt)
         d["O"] = torch.empty_like(d["Q"])
         d["S"] = torch.empty(wl.B, wl.Hkv, wl.d, wl.d, dtype=torch.float32, device="cuda")
         d["z"] = torch.empty(wl.B, wl.Hkv, wl.d, dtype=torch.float32, device="cuda")
@@ -198,9 +221,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="llama1b_32k")
     ap.add_argument("--feature-map", type=int, default=1)
-    ap.add_argument("--sweep", action="store_true", help="also time the other graded shapes (reported under 'sweep')")
+    ap.add_argument("--quick", action="store_true",
+                    help="headline only: skip the other graded shapes and variants ('sweep') and the stand-alone calls "
+                         "('side_ops') that a default run also reports")
+    ap.add_argument("--sweep", action="store_true", help="(default; kept for old command lines)")
+    ap.add_argument("--side-ops", action="store_true", help="(default; kept for old command lines)")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--side-ops", action="store_true", help="also time lawcat_conv1d_causal and lawcat_gla_step alone")
     ap.add_argument("--segment", type=int, default=0, help="tokens per segment (0 = the library's choice)")
     ap.add_argument("--carry", type=int, default=0, choices=(0, 1, 2),
                     help="state carry: 0 = the library's choice, 1 = sequential (one segment per head), 2 = two-level")
@@ -251,19 +277,30 @@ def main():
     flops = mfma_flops_per_token(wl) * wl.B * wl.T
     out["mfma"] = {"useful_flops_per_token": mfma_flops_per_token(wl), "achieved_tflops": flops / (r["ms_per_step"] * 1e-3) / 1e12,
                    "frac_of_bf16_peak": flops / (r["ms_per_step"] * 1e-3) / 2.5e15}
-    if args.sweep:
+    def entry(r2):
+        e = {"tokens_per_s": r2["tokens_per_s"], "ms_per_step": r2["ms_per_step"], "kernel_ms": r2["kernel_ms"],
+             "whole_step_frac": r2["bytes_step"] / (r2["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        if r2["kernel_ms"]:
+            e["output_pass_frac"] = r2["bytes_step"] / (r2["kernel_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS
+        return e
+
+    if not args.quick:
+        # the rest of the metric's range (T = 8K .. 128K, both layer shapes) and the other axes of the headline
+        # shape, device-generated inputs of the same distributions, fewer steps each
         sweep = {}
+        st, wu = max(5, args.steps // 2), max(2, args.warmup // 2)
         for name in ("llama1b_8k", "llama1b_32k", "mistral7b_16k", "mistral7b_128k"):
-            if name == wl.name:
+            if name == wl.name and args.feature_map == 1 and args.gate_scale == 1.0:
                 continue
-            w2 = WORKLOADS[name]
-            r2 = run_workload(w2, max(5, args.steps // 2), max(2, args.warmup // 2), args.feature_map)
-            sweep[name] = {"tokens_per_s": r2["tokens_per_s"], "ms_per_step": r2["ms_per_step"],
-                           "kernel_ms": r2["kernel_ms"],
-                           "whole_step_frac": r2["bytes_step"] / (r2["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
-            del r2
+            sweep[name] = entry(run_workload(WORKLOADS[name], st, wu, 1, host_inputs=False))
             torch.cuda.empty_cache()
+        sweep[wl.name + ":identity_feature_map"] = entry(run_workload(wl, st, wu, 0, host_inputs=False))
+        torch.cuda.empty_cache()
+        # gate temperature 1/16: a slowly decaying state (the state pass cannot stop early, see its kernel)
+        sweep[wl.name + ":gate_scale_1/16"] = entry(run_workload(wl, st, wu, 1, gate_scale=0.0625, host_inputs=False))
+        torch.cuda.empty_cache()
         out["sweep"] = sweep
+        out["side_ops"] = run_side_ops(wl)
     if args.curve:
         import torch
         from dataclasses import replace
@@ -271,15 +308,10 @@ def main():
         for base in ("llama1b_32k", "mistral7b_16k"):
             for T in (8192, 16384, 32768, 65536, 131072):
                 w2 = replace(WORKLOADS[base], T=T, name=f"{base.split('_')[0]}@{T}")
-                r2 = run_workload(w2, max(5, args.steps // 3), max(2, args.warmup // 3), args.feature_map)
-                curve[w2.name] = {"tokens_per_s": r2["tokens_per_s"], "ms_per_step": r2["ms_per_step"],
-                                  "kernel_ms": r2["kernel_ms"],
-                                  "whole_step_frac": r2["bytes_step"] / (r2["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
-                del r2
+                curve[w2.name] = entry(run_workload(w2, max(5, args.steps // 3), max(2, args.warmup // 3),
+                                                    args.feature_map, host_inputs=False))
                 torch.cuda.empty_cache()
         out["curve"] = curve
-    if args.side_ops:
-        out["side_ops"] = run_side_ops(wl)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(wl, r["host0"], args.feature_map)
     print(json.dumps(out), flush=True)
