@@ -177,7 +177,24 @@ def run_side_ops(wl, steps=30):
     e1.record()
     torch.cuda.synchronize()
     step_us = e0.elapsed_time(e1) / n * 1e3
-    return {"conv1d_causal_q": {"ms": conv_ms, "GB/s": conv_bytes / (conv_ms * 1e-3) / 1e9,
+    # the same decode in blocks of 256 tokens per launch (state on chip between the steps)
+    nb = 256
+    dn = lawcat.make_desc(wl.B, nb, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W, dtype=lawcat.DTYPE_BF16, feature_map=1)
+    qn = torch.rand(wl.B, nb, wl.Hq, wl.d, device="cuda").to(dt) + 0.5
+    kn = torch.rand(wl.B, nb, wl.Hkv, wl.d, device="cuda").to(dt) + 0.5
+    vn = torch.randn(wl.B, nb, wl.Hkv, wl.d, device="cuda").to(dt)
+    gn = torch.randn(wl.B, nb, wl.Hkv, wl.d, device="cuda").to(dt)
+    on = torch.empty_like(qn)
+    for _ in range(2):
+        lawcat.gla_steps(dn, qn, kn, vn, gn, S, z, on)
+    e0.record()
+    for _ in range(10):
+        lawcat.gla_steps(dn, qn, kn, vn, gn, S, z, on)
+    e1.record()
+    torch.cuda.synchronize()
+    block_us = e0.elapsed_time(e1) / (10 * nb) * 1e3
+    return {"gla_steps_block256": {"us_per_step": block_us},
+            "conv1d_causal_q": {"ms": conv_ms, "GB/s": conv_bytes / (conv_ms * 1e-3) / 1e9,
                                 "frac_of_hbm_peak": conv_bytes / (conv_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "gla_step": {"us_per_step": step_us, "state_bytes_per_step": 2 * S.numel() * 4}}
 

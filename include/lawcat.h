@@ -119,6 +119,18 @@ LAWCAT_API int lawcat_gla_step(const lawcat_desc* desc, const void* q, const voi
                     const void* gate_logits, float* S, float* z, void* o, void* stream);
 
 /*
+ * Section 4.2, n = desc->T consecutive recurrent (decode) steps per sequence in ONE launch: the same fp32
+ * token-by-token arithmetic as n calls of lawcat_gla_step, with the state held on chip between the steps, so
+ * the state's 2 * Hkv * dk * dv * 4 bytes cross HBM once per call instead of once per token (streaming
+ * inference in blocks of tokens, speculative or chunked decoding).
+ *   q [B,n,Hq,dk]  k, gate_logits [B,n,Hkv,dk]  v [B,n,Hkv,dv]  o [B,n,Hq,dv]
+ *   S [B,Hkv,dk,dv], z [B,Hkv,dk]: read, updated in place to the state after the n-th token.
+ * q and k are the already transformed q-dot, k-dot (lawcat_conv1d_causal with T = n and the conv cache as halo).
+ */
+LAWCAT_API int lawcat_gla_steps(const lawcat_desc* desc, const void* q, const void* k, const void* v,
+                     const void* gate_logits, float* S, float* z, void* o, void* stream);
+
+/*
  * The whole layer of Fig. 1 between the projections: conv + phi on Q (weights wq [Hq,dk,W])
  * and on K (wk [Hkv,dk,W]), gate logits -> decay, normalized gated linear attention.
  * Equals lawcat_conv1d_causal on Q and on K followed by lawcat_gla_prefill.

@@ -169,6 +169,21 @@ int lawcat_gla_step(const lawcat_desc* desc, const void* q, const void* k, const
   return hip_status(launch_gla_step(r, static_cast<hipStream_t>(stream)));
 }
 
+int lawcat_gla_steps(const lawcat_desc* desc, const void* q, const void* k, const void* v, const void* gate_logits,
+                     float* S, float* z, void* o, void* stream) {
+  int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (!q || !k || !v || !gate_logits || !S || !z || !o) return LAWCAT_E_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(gate_logits) || !aligned16(S) ||
+      !aligned16(z) || !aligned16(o))
+    return LAWCAT_E_ALIGN;
+  RecurrentParams r{};
+  r.q = q; r.k = k; r.v = v; r.g = gate_logits; r.S0 = S; r.z0 = z; r.o = o; r.den_out = nullptr;
+  r.S_out = S; r.z_out = z; r.B = desc->B; r.T = desc->T; r.Hq = desc->Hq; r.Hkv = desc->Hkv; r.d = desc->dk;
+  r.gate_scale = desc->gate_scale; r.eps = desc->eps; r.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
+  return hip_status(launch_gla_steps(r, static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"
 
 namespace {

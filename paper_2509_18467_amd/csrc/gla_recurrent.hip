@@ -54,35 +54,67 @@ __global__ void __launch_bounds__(256) gla_recurrent_kernel(
   }
   if (NJ * 16 == D) __syncthreads();  // in-place update: every read of S/z precedes every write
 
-  for (int t = 0; t < Tn; ++t) {
+  // One token's operands of this thread: its key channels of k and g, its value columns of v, and its key channels
+  // of the first HB query heads of the group.  They are requested one token ahead, so that a token costs one
+  // memory round trip hidden behind the previous token's arithmetic instead of five exposed ones.
+  constexpr int HB = 4;
+  struct Tok { float k[R], g[R], v[NJ], q[HB][R]; };
+  const int nhb = group < HB ? group : HB;
+  auto load_tok = [&](int t, Tok& x) {
     const size_t tok = (size_t)b * Tn + t;
     const T* kt = k + (tok * Hkv + hk) * D;
     const T* gt = g + (tok * Hkv + hk) * D;
     const T* vt = v + (tok * Hkv + hk) * D;
-    float vv[NJ];
 #pragma unroll
-    for (int s = 0; s < NJ; ++s) vv[s] = ldf(vt + (slice0 + s) * 16 + j);
+    for (int r = 0; r < R; ++r) { x.k[r] = ldf(kt + cg + 16 * r); x.g[r] = ldf(gt + cg + 16 * r); }
+#pragma unroll
+    for (int s = 0; s < NJ; ++s) x.v[s] = ldf(vt + (slice0 + s) * 16 + j);
+#pragma unroll
+    for (int hh = 0; hh < HB; ++hh)
+      if (hh < nhb) {
+        const T* qt = q + (tok * Hq + hk * group + hh) * D;
+#pragma unroll
+        for (int r = 0; r < R; ++r) x.q[hh][r] = ldf(qt + cg + 16 * r);
+      }
+  };
+  Tok cur, nxt;
+  load_tok(0, cur);
+  const bool gs1 = gate_scale == 1.0f;
+  for (int t = 0; t < Tn; ++t) {
+    const size_t tok = (size_t)b * Tn + t;
+    if (t + 1 < Tn) load_tok(t + 1, nxt);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const int c = cg + 16 * r;
-      const float alpha = expf(gate_scale * log_sigmoid(ldf(gt + c)));
-      const float kk = ldf(kt + c);
+      // alpha = sigmoid(g)^gate_scale; at gate_scale 1 directly 1 / (1 + e^-g)
+      const float alpha = gs1 ? 1.f / (1.f + expf(-cur.g[r])) : expf(gate_scale * log_sigmoid(cur.g[r]));
+      const float kk = cur.k[r];
       z[r] = fmaf(alpha, z[r], kk);
 #pragma unroll
-      for (int s = 0; s < NJ; ++s) S[s][r] = fmaf(alpha, S[s][r], kk * vv[s]);
+      for (int s = 0; s < NJ; ++s) S[s][r] = fmaf(alpha, S[s][r], kk * cur.v[s]);
     }
     for (int hh = 0; hh < group; ++hh) {
       const int hq = hk * group + hh;
-      const T* qt = q + (tok * Hq + hq) * D;
+      float qq[R];
+      if (hh < HB) {
+#pragma unroll
+        for (int h2 = 0; h2 < HB; ++h2)
+          if (h2 == hh) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) qq[r] = cur.q[h2][r];
+          }
+      } else {
+        const T* qt = q + (tok * Hq + hq) * D;
+#pragma unroll
+        for (int r = 0; r < R; ++r) qq[r] = ldf(qt + cg + 16 * r);
+      }
       float pd = 0.f, pn[NJ];
 #pragma unroll
       for (int s = 0; s < NJ; ++s) pn[s] = 0.f;
 #pragma unroll
       for (int r = 0; r < R; ++r) {
-        const float qq = ldf(qt + cg + 16 * r);
-        pd = fmaf(qq, z[r], pd);
+        pd = fmaf(qq[r], z[r], pd);
 #pragma unroll
-        for (int s = 0; s < NJ; ++s) pn[s] = fmaf(qq, S[s][r], pn[s]);
+        for (int s = 0; s < NJ; ++s) pn[s] = fmaf(qq[r], S[s][r], pn[s]);
       }
 #pragma unroll
       for (int m = 8; m >= 1; m >>= 1) {
@@ -98,6 +130,7 @@ __global__ void __launch_bounds__(256) gla_recurrent_kernel(
         if (den_out != nullptr && j == 0 && slice0 == 0) den_out[tok * Hq + hq] = den;
       }
     }
+    cur = nxt;
   }
 #pragma unroll
   for (int r = 0; r < R; ++r) {
@@ -199,6 +232,22 @@ hipError_t launch_d(const RecurrentParams& p, hipStream_t stream) {
 }
 
 }  // namespace
+
+// n consecutive decode steps in one launch: the token-by-token kernel with one block per (batch, kv head) that
+// owns every value column (NJ = D / 16), so the state stays in registers for all n tokens and the in-place
+// update is safe (every read of S and z precedes every write inside the one block that touches them).
+template <typename T, int D>
+hipError_t launch_steps_d(const RecurrentParams& p, hipStream_t stream) {
+  hipLaunchKernelGGL((gla_recurrent_kernel<T, D, D / 16>), dim3(p.B * p.Hkv, 1), dim3(256), 0, stream, (const T*)p.q,
+                     (const T*)p.k, (const T*)p.v, (const T*)p.g, p.S_out, p.z_out, (T*)p.o, (float*)nullptr, p.S_out,
+                     p.z_out, p.T, p.Hq, p.Hkv, p.gate_scale, p.eps);
+  return hipGetLastError();
+}
+
+hipError_t launch_gla_steps(const RecurrentParams& p, hipStream_t stream) {
+  if (p.bf16) return p.d == 64 ? launch_steps_d<bf16_t, 64>(p, stream) : launch_steps_d<bf16_t, 128>(p, stream);
+  return p.d == 64 ? launch_steps_d<float, 64>(p, stream) : launch_steps_d<float, 128>(p, stream);
+}
 
 hipError_t launch_gla_step(const RecurrentParams& p, hipStream_t stream) {
   if (p.bf16) return p.d == 64 ? launch_step_d<bf16_t, 64>(p, stream) : launch_step_d<bf16_t, 128>(p, stream);

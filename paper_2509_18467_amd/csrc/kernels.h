@@ -40,6 +40,8 @@ struct RecurrentParams {
 hipError_t launch_gla_recurrent(const RecurrentParams& p, hipStream_t stream);
 // One token per sequence, S_out/z_out updated in place (S0, z0, den_out, T are not read).
 hipError_t launch_gla_step(const RecurrentParams& p, hipStream_t stream);
+// T consecutive tokens per sequence in one launch, S_out/z_out updated in place (S0, z0, den_out are not read).
+hipError_t launch_gla_steps(const RecurrentParams& p, hipStream_t stream);
 
 // How the bf16 matrix-core prefill splits a sequence: `nseg` segments of `seg_len` tokens per
 // (batch, kv head), each carried sequentially by one workgroup.  With nseg > 1 a first pass

@@ -20,7 +20,7 @@ CARRY_AUTO, CARRY_SEQUENTIAL, CARRY_TWO_LEVEL = 0, 1, 2
 CALL_CONV1D, CALL_GLA_PREFILL, CALL_GLA_STEP, CALL_LAYER_PREFILL = 0, 1, 2, 3
 
 EXPORTS = (
-    "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gla_prefill", "lawcat_gla_step",
+    "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gla_prefill", "lawcat_gla_step", "lawcat_gla_steps",
     "lawcat_layer_prefill", "lawcat_layer_prefill_static", "lawcat_layer_prefill_timed", "lawcat_status_string", "lawcat_version",
 )
 
@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.lawcat_gla_prefill.restype = ci
         L.lawcat_gla_step.argtypes = [dp] + [vp] * 8
         L.lawcat_gla_step.restype = ci
+        L.lawcat_gla_steps.argtypes = [dp] + [vp] * 8
+        L.lawcat_gla_steps.restype = ci
         L.lawcat_layer_prefill.argtypes = [dp] + [vp] * 17 + [sz, vp]
         L.lawcat_layer_prefill.restype = ci
         L.lawcat_status_string.argtypes = [ci]
@@ -126,6 +128,11 @@ def gla_prefill(desc, q, k, v, gate_logits, S0, z0, o, den_out, S_out, z_out, wo
 def gla_step(desc, q, k, v, gate_logits, S, z, o, stream=None):
     _check(lib().lawcat_gla_step(ctypes.byref(desc), _p(q), _p(k), _p(v), _p(gate_logits), _p(S), _p(z), _p(o),
                                  _stream(stream)))
+
+
+def gla_steps(desc, q, k, v, gate_logits, S, z, o, stream=None):
+    _check(lib().lawcat_gla_steps(ctypes.byref(desc), _p(q), _p(k), _p(v), _p(gate_logits), _p(S), _p(z), _p(o),
+                                  _stream(stream)))
 
 
 def layer_prefill(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,

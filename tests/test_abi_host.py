@@ -133,6 +133,18 @@ def test_status_strings():
         lawcat._check(-3)
 
 
+def test_gla_steps_argument_checks():
+    L = lawcat.lib()
+    d = lawcat.make_desc(1, 8, 4, 2, 64)
+    ok = [A] * 7
+    assert L.lawcat_gla_steps(None, *ok, None) == -1
+    assert L.lawcat_gla_steps(ctypes.byref(d), None, *ok[1:], None) == -1
+    assert L.lawcat_gla_steps(ctypes.byref(d), *ok[:4], None, A, A, None) == -1
+    assert L.lawcat_gla_steps(ctypes.byref(d), ctypes.c_void_p(0x1004), *ok[1:], None) == -5
+    assert L.lawcat_gla_steps(ctypes.byref(lawcat.make_desc(1, 0, 4, 2, 64)), *ok, None) == -2
+    assert L.lawcat_gla_steps(ctypes.byref(lawcat.make_desc(1, 8, 4, 2, 96)), *ok, None) == -3
+
+
 def test_static_entry_point_rejects_what_its_buffer_cannot_hold():
     """lawcat_layer_prefill_static checks the desc and the scratch need before anything else."""
     L = lawcat.lib()

@@ -333,6 +333,43 @@ def _decode(oracle, wl, x_new, state_gpu, state_ref, heads=None):
     return got, ref
 
 
+def _decode_block(oracle, wl, x_new, state_gpu, state_ref):
+    """The same n decode steps in two launches: the conv over the n new tokens with the cache as halo, then
+    lawcat_gla_steps (n recurrent steps with the state on chip)."""
+    dt = H.tdtype(wl)
+    n = x_new["Q"].shape[1]
+    dn = H.desc_for(wl.with_T(n), feature_map=1)
+    wq, wk = H.dev(x_new["wq"], dt), H.dev(x_new["wk"], dt)
+    S, z = H.dev(state_gpu["S"]), H.dev(state_gpu["z"])
+    qc, kc = H.dev(state_gpu["q_tail"], dt), H.dev(state_gpu["k_tail"], dt)
+    qc2, kc2 = torch.empty_like(qc), torch.empty_like(kc)
+    Qd, Kd, Vd, Gd = (H.dev(x_new[k], dt) for k in "QKVG")
+    qdot, kdot = torch.empty_like(Qd), torch.empty_like(Kd)
+    o = torch.empty_like(Qd)
+    lawcat.conv1d_causal(dn, wl.Hq, Qd, wq, qc, qdot, qc2)
+    lawcat.conv1d_causal(dn, wl.Hkv, Kd, wk, kc, kdot, kc2)
+    lawcat.gla_steps(dn, qdot, kdot, Vd, Gd, S, z, o)
+    torch.cuda.synchronize()
+    got = {"o": H.host(o), "S": H.host(S), "z": H.host(z), "q_tail": H.host(qc2), "k_tail": H.host(kc2)}
+    ref = oracle.layer_prefill(x_new["Q"], x_new["K"], x_new["V"], x_new["G"], x_new["wq"], x_new["wk"], 1, 1.0, 0.0,
+                               state_ref["S"], state_ref["z"], state_ref["q_tail"], state_ref["k_tail"])
+    return got, ref
+
+
+@pytest.mark.parametrize("name,T,n", [("tiny", 256, 40), ("llama1b_8k", 300, 33), ("mistral7b_16k", 200, 17)])
+def test_prefill_then_a_block_of_decode_steps(oracle, name, T, n):
+    wl = WORKLOADS[name].with_T(T)
+    x = make_inputs(wl, seed=4)
+    xn = make_inputs(wl.with_T(n), seed=5)
+    xn["wq"], xn["wk"] = x["wq"], x["wk"]
+    a = H.run_layer_prefill(wl, x)
+    ra = oracle.layer_prefill(x["Q"], x["K"], x["V"], x["G"], x["wq"], x["wk"], 1)
+    got, ref = _decode_block(oracle, wl, xn, a, ra)
+    for k in ("o", "S", "z"):
+        H.assert_close(got[k], ref[k], wl, "decode block " + k)
+    assert np.array_equal(got["q_tail"], ref["q_tail"]) and np.array_equal(got["k_tail"], ref["k_tail"])
+
+
 @pytest.mark.parametrize("name,T,n", [("tiny", 256, 24), ("llama1b_8k", 300, 16), ("mistral7b_16k", 200, 16)])
 def test_prefill_then_decode_steps(oracle, name, T, n):
     wl = WORKLOADS[name].with_T(T)
@@ -372,3 +409,8 @@ def test_stress_128k_then_256_steps(oracle, phi):
     H.assert_close(gd["o"], rd["o"], wl, "stress decode o")
     H.assert_close(gd["S"], rd["S"], wl, "stress decode S")
     H.assert_close(gd["z"], rd["z"], wl, "stress decode z")
+    # the same 256 steps in one lawcat_gla_steps call
+    gb, _ = _decode_block(oracle, wl, xn, got, ref)
+    H.assert_close(gb["o"], rd["o"], wl, "stress decode block o")
+    H.assert_close(gb["S"], rd["S"], wl, "stress decode block S")
+    H.assert_close(gb["z"], rd["z"], wl, "stress decode block z")
