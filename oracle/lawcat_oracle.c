@@ -11,6 +11,8 @@
  *       x~_t = sum_{delta=0..r} w_delta * x_{t-delta}   (the "simplest case" sum)
  *     followed by an optional pointwise positive map (1+ELU, named in section 2
  *     as an example of phi).
+ *   - section 4.1, optionally: the linear layer with nonlinearity that follows the conv, shared by query and key,
+ *       q-dot = phi(q~ Wf), k-dot = phi(k~ Wf)
  *   - section 4.2, KV-state update equation (first equation of 4.2):
  *       S_t = G_t (.) S_{t-1} + k_t^T v_t ,  S_0 = 0 unless a start state is given
  *     with the gate per key channel (G_t = alpha_t^T 1), alpha_t = sigmoid(g_t)^gate_scale,
@@ -69,6 +71,29 @@ void lawcat_oracle_conv1d_causal(int B, int T, int H, int d, int W, const double
           }
           y[(((size_t)b * T + t) * H + h) * d + c] = feature_map(acc, phi);
         }
+}
+
+/*
+ * Section 4.1, the layer after the conv: "a linear layer with nonlinearity", the same for the query and the key.
+ *   y[b,t,h,f] = phi( sum_c x[b,t,h,c] * wf[h / group, c, f] )
+ * x: [B,T,H,d] (the conv output, no nonlinearity applied yet); wf: [H/group, d, d]: one matrix per group of
+ * `group` consecutive heads (group = 1 for key heads, Hq/Hkv for query heads, so that a key head and the query
+ * heads that read its state share one matrix); y: [B,T,H,d].
+ */
+void lawcat_oracle_feature_linear(int B, int T, int H, int d, int group, const double* x, const double* wf,
+                                  int phi, double* y) {
+  for (int b = 0; b < B; ++b)
+    for (int t = 0; t < T; ++t)
+      for (int h = 0; h < H; ++h) {
+        const double* xr = x + (((size_t)b * T + t) * H + h) * d;
+        const double* w = wf + (size_t)(h / group) * d * d;
+        double* yr = y + (((size_t)b * T + t) * H + h) * d;
+        for (int f = 0; f < d; ++f) {
+          double acc = 0.0;
+          for (int c = 0; c < d; ++c) acc += xr[c] * w[(size_t)c * d + f];
+          yr[f] = feature_map(acc, phi);
+        }
+      }
 }
 
 /*

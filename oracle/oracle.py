@@ -41,6 +41,8 @@ def _load():
             [ctypes.c_int] * 6 + [dp] * 4 + [ctypes.c_double] * 2 + [dp] * 7
         )
         _lib.lawcat_oracle_gla_prefill.restype = None
+        _lib.lawcat_oracle_feature_linear.argtypes = [ctypes.c_int] * 5 + [dp, dp, ctypes.c_int, dp]
+        _lib.lawcat_oracle_feature_linear.restype = None
         _lib.lawcat_oracle_max_threads.restype = ctypes.c_int
     return _lib
 
@@ -71,6 +73,20 @@ def conv1d_causal(x, w, halo=None, feature_map: int = 0):
         assert halo.shape == (B, W - 1, H, d)
     y = np.empty_like(x)
     lib.lawcat_oracle_conv1d_causal(B, T, H, d, W, _ptr(x), _ptr(w), _ptr(halo), int(feature_map), _ptr(y))
+    return y
+
+
+def feature_linear(x, wf, feature_map: int = 0):
+    """Section 4.1: y = phi(x Wf) per head; x [B,T,H,d], wf [Hw,d,d] with H % Hw == 0: head h uses matrix
+    h // (H // Hw), so a key head and the query heads of its group share one matrix."""
+    lib = _load()
+    x = _f64(x)
+    wf = _f64(wf)
+    B, T, H, d = x.shape
+    Hw = wf.shape[0]
+    assert wf.shape == (Hw, d, d) and H % Hw == 0
+    y = np.empty_like(x)
+    lib.lawcat_oracle_feature_linear(B, T, H, d, H // Hw, _ptr(x), _ptr(wf), int(feature_map), _ptr(y))
     return y
 
 
@@ -118,11 +134,16 @@ def _tail(x, halo, W):
 
 
 def layer_prefill(Q, K, V, G, wq, wk, feature_map: int = 0, gate_scale: float = 1.0, eps: float = 0.0,
-                  S0=None, z0=None, q_halo=None, k_halo=None):
-    """Conv1D on Q and on K (section 4.1), phi, then normalized GLA (section 4.2)."""
+                  S0=None, z0=None, q_halo=None, k_halo=None, wf=None):
+    """Conv1D on Q and on K (section 4.1), phi -- pointwise, or after the shared linear layer wf [Hkv,d,d] --
+    then normalized GLA (section 4.2)."""
     W = np.asarray(wq).shape[-1]
-    qd = conv1d_causal(Q, wq, q_halo, feature_map)
-    kd = conv1d_causal(K, wk, k_halo, feature_map)
+    if wf is None:
+        qd = conv1d_causal(Q, wq, q_halo, feature_map)
+        kd = conv1d_causal(K, wk, k_halo, feature_map)
+    else:
+        qd = feature_linear(conv1d_causal(Q, wq, q_halo, 0), wf, feature_map)
+        kd = feature_linear(conv1d_causal(K, wk, k_halo, 0), wf, feature_map)
     r = gla_prefill(qd, kd, V, G, gate_scale, eps, S0, z0)
     r["q_tail"] = _tail(Q, q_halo, W)
     r["k_tail"] = _tail(K, k_halo, W)

@@ -272,6 +272,39 @@ def test_feature_map_one_plus_elu(oracle):
 
 
 # ---------------------------------------------------------------- composition
+def test_shared_linear_feature_map(oracle):
+    """The linear layer with nonlinearity after the conv (section 4.1), one matrix per kv head shared by the key
+    head and its query heads: equals a library matmul; the identity matrix gives back the pointwise map; the
+    whole layer with it equals conv -> matmul -> phi -> attention assembled by hand."""
+    rng = np.random.default_rng(12)
+    B, T, Hq, Hkv, d = 2, 9, 4, 2, 5
+    x = _rand(rng, B, T, Hq, d)
+    wf = _rand(rng, Hkv, d, d)
+    for phi in (0, 1):
+        y = oracle.feature_linear(x, wf, phi)
+        for h in range(Hq):
+            lin = x[:, :, h] @ wf[h // (Hq // Hkv)]          # head h uses the matrix of its kv head
+            ref = lin if phi == 0 else np.where(lin > 0, 1.0 + lin, np.exp(np.minimum(lin, 0.0)))
+            np.testing.assert_allclose(y[:, :, h], ref, rtol=1e-13, atol=1e-13)
+    eye = np.broadcast_to(np.eye(d), (Hkv, d, d)).copy()
+    np.testing.assert_allclose(oracle.feature_linear(x, eye, 1), np.where(x > 0, 1 + x, np.exp(np.minimum(x, 0))), atol=1e-15)
+    # a transposed weight or a wrong head mapping must show: asymmetric matrix, different per kv head
+    assert np.abs(oracle.feature_linear(x, wf, 0) - oracle.feature_linear(x, np.swapaxes(wf, 1, 2), 0)).max() > 0.1
+    assert np.abs(oracle.feature_linear(x, wf, 0) - oracle.feature_linear(x, wf[::-1], 0)).max() > 0.1
+    # the fused layer: conv, then the shared matrix on q and on k, then phi, then the attention
+    Q, K, V, G = _rand(rng, B, T, Hq, d), _rand(rng, B, T, Hkv, d), _rand(rng, B, T, Hkv, d), _rand(rng, B, T, Hkv, d)
+    wq, wk = _rand(rng, Hq, d, 4), _rand(rng, Hkv, d, 4)
+    r = oracle.layer_prefill(Q, K, V, G, wq, wk, 1, wf=wf)
+    qd = oracle.feature_linear(oracle.conv1d_causal(Q, wq), wf, 1)
+    kd = oracle.feature_linear(oracle.conv1d_causal(K, wk), wf, 1)
+    r2 = oracle.gla_prefill(qd, kd, V, G)
+    np.testing.assert_allclose(r["o"], r2["o"], rtol=0, atol=1e-14)
+    # with the identity matrix the layer is the pointwise-map layer
+    r3 = oracle.layer_prefill(Q, K, V, G, wq, wk, 1, wf=np.broadcast_to(np.eye(d), (Hkv, d, d)).copy())
+    r4 = oracle.layer_prefill(Q, K, V, G, wq, wk, 1)
+    np.testing.assert_allclose(r3["o"], r4["o"], rtol=0, atol=1e-13)
+
+
 def test_continuation_split_prefill_and_steps(oracle):
     """prefill(T) == prefill(T1) then prefill(T-T1) with carried (S, z, conv tails) == T single steps."""
     rng = np.random.default_rng(12)
