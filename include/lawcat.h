@@ -64,7 +64,8 @@ enum {
   LAWCAT_CALL_CONV1D = 0,
   LAWCAT_CALL_GLA_PREFILL = 1,
   LAWCAT_CALL_GLA_STEP = 2,
-  LAWCAT_CALL_LAYER_PREFILL = 3
+  LAWCAT_CALL_LAYER_PREFILL = 3,
+  LAWCAT_CALL_LAYER_PREFILL_FM = 4
 };
 
 typedef struct lawcat_desc {
@@ -95,6 +96,18 @@ LAWCAT_API size_t lawcat_workspace_bytes(const lawcat_desc* desc, int which_call
  */
 LAWCAT_API int lawcat_conv1d_causal(const lawcat_desc* desc, int n_heads, const void* x, const void* w,
                          const void* halo, void* y, void* tail_out, void* stream);
+
+/*
+ * Section 4.1 with the shared linear layer after the conv ("a linear layer with nonlinearity", the same
+ * for the query and the key):
+ *   y[b,t,h,f] = phi( sum_c x~[b,t,h,c] * wf[h / group, c, f] ),   x~ = the conv of lawcat_conv1d_causal without phi
+ *   wf [Hkv,d,d] in the storage type, row-major [c][f]; n_heads must be a multiple of desc->Hkv and
+ *   group = n_heads / desc->Hkv: a query head uses the matrix of the kv head whose state it reads.
+ * Every other argument as in lawcat_conv1d_causal.  bf16 storage: x~ is rounded to bf16 once, as the
+ * matrix-core operand; accumulation in fp32.
+ */
+LAWCAT_API int lawcat_conv1d_feature(const lawcat_desc* desc, int n_heads, const void* x, const void* w,
+                          const void* wf, const void* halo, void* y, void* tail_out, void* stream);
 
 /*
  * Section 4.2, prefill: for t = 1..T
@@ -142,6 +155,22 @@ LAWCAT_API int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, cons
                          const float* z0, const void* q_halo, const void* k_halo, void* O,
                          float* den_out, float* S_out, float* z_out, void* q_tail_out,
                          void* k_tail_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The layer of Fig. 1 with the feature map of section 4.1 in full: after the conv, "a linear layer with
+ * nonlinearity", the same for the query and the key,
+ *   q-dot = phi( conv(Q) Wf ),  k-dot = phi( conv(K) Wf ),
+ * then the attention of section 4.2: lawcat_conv1d_feature on Q and on K followed by lawcat_gla_prefill.
+ * wf [Hkv,dk,dk] as in lawcat_conv1d_feature; with identity matrices the call equals lawcat_layer_prefill.
+ * Every other argument as in lawcat_layer_prefill; workspace from
+ * lawcat_workspace_bytes(desc, LAWCAT_CALL_LAYER_PREFILL_FM): q-dot and k-dot are staged there in the storage
+ * type, B*T*(Hq+Hkv)*dk elements, ahead of what lawcat_gla_prefill needs.
+ */
+LAWCAT_API int lawcat_layer_prefill_fm(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
+                            const void* gate_logits, const void* wq, const void* wk, const void* wf,
+                            const float* S0, const float* z0, const void* q_halo, const void* k_halo, void* O,
+                            float* den_out, float* S_out, float* z_out, void* q_tail_out, void* k_tail_out,
+                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * lawcat_layer_prefill for callers that cannot allocate device memory or hold a workspace: code under HIP

@@ -91,6 +91,13 @@ size_t workspace_bytes_checked(const lawcat_desc* d, int which) {
       const size_t rows = (size_t)d->B * d->T;
       return align_up(rows * d->Hq * d->dk * elem_bytes(d), 256) + align_up(rows * d->Hkv * d->dk * elem_bytes(d), 256);
     }
+    case LAWCAT_CALL_LAYER_PREFILL_FM: {
+      // q-dot and k-dot staged in the storage type, then whatever lawcat_gla_prefill needs
+      const size_t rows = (size_t)d->B * d->T;
+      const size_t inner = prefill_path(d) == Path::kChunkBf16 ? plan_for(d).workspace_bytes : 0;
+      return align_up(rows * d->Hq * d->dk * elem_bytes(d), 256) + align_up(rows * d->Hkv * d->dk * elem_bytes(d), 256) +
+             align_up(inner, 256);
+    }
     default:
       return 0;
   }
@@ -122,6 +129,24 @@ int lawcat_conv1d_causal(const lawcat_desc* desc, int n_heads, const void* x, co
   p.B = desc->B; p.T = desc->T; p.H = n_heads; p.d = desc->dk; p.W = desc->conv_width;
   p.phi = desc->feature_map; p.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
   return hip_status(launch_conv1d(p, static_cast<hipStream_t>(stream)));
+}
+
+int lawcat_conv1d_feature(const lawcat_desc* desc, int n_heads, const void* x, const void* w, const void* wf,
+                          const void* halo, void* y, void* tail_out, void* stream) {
+  int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (n_heads <= 0 || n_heads % desc->Hkv != 0) return LAWCAT_E_BAD_DESC;
+  if (x == nullptr || w == nullptr || wf == nullptr || y == nullptr) return LAWCAT_E_NULL;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(wf) || !aligned16(y) || !aligned16(halo) || !aligned16(tail_out))
+    return LAWCAT_E_ALIGN;
+  ConvParams p{};
+  p.x = x; p.w = w; p.halo = desc->conv_width > 1 ? halo : nullptr; p.y = y;
+  p.tail_out = desc->conv_width > 1 ? tail_out : nullptr;
+  p.B = desc->B; p.T = desc->T; p.H = n_heads; p.d = desc->dk; p.W = desc->conv_width;
+  p.phi = desc->feature_map; p.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  if (launch_conv_feature(p, wf, n_heads / desc->Hkv, hs) != hipSuccess) return LAWCAT_E_HIP;
+  return hip_status(launch_conv_tail(p, hs));
 }
 
 int lawcat_gla_prefill(const lawcat_desc* desc, const void* q, const void* k, const void* v,
@@ -253,6 +278,36 @@ int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, 
                          size_t workspace_bytes, void* stream) {
   return layer_prefill_impl(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,
                             q_tail_out, k_tail_out, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+int lawcat_layer_prefill_fm(const lawcat_desc* desc, const void* Q, const void* K, const void* V,
+                            const void* gate_logits, const void* wq, const void* wk, const void* wf, const float* S0,
+                            const float* z0, const void* q_halo, const void* k_halo, void* O, float* den_out,
+                            float* S_out, float* z_out, void* q_tail_out, void* k_tail_out, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (!Q || !K || !V || !gate_logits || !wq || !wk || !wf || !O || !S_out || !z_out) return LAWCAT_E_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(gate_logits) || !aligned16(wq) ||
+      !aligned16(wk) || !aligned16(wf) || !aligned16(S0) || !aligned16(z0) || !aligned16(q_halo) ||
+      !aligned16(k_halo) || !aligned16(O) || !aligned16(den_out) || !aligned16(S_out) || !aligned16(z_out) ||
+      !aligned16(q_tail_out) || !aligned16(k_tail_out) || !aligned16(workspace))
+    return LAWCAT_E_ALIGN;
+  const size_t need = workspace_bytes_checked(desc, LAWCAT_CALL_LAYER_PREFILL_FM);
+  if (workspace == nullptr || workspace_bytes < need) return LAWCAT_E_WORKSPACE;
+  const size_t rows = (size_t)desc->B * desc->T;
+  char* ws = static_cast<char*>(workspace);
+  void* qd = ws;
+  void* kd = ws + align_up(rows * desc->Hq * desc->dk * elem_bytes(desc), 256);
+  char* inner = static_cast<char*>(kd) + align_up(rows * desc->Hkv * desc->dk * elem_bytes(desc), 256);
+  const size_t inner_bytes = workspace_bytes - (size_t)(inner - ws);
+  // queries: each head with the matrix of the kv head whose state it reads
+  st = lawcat_conv1d_feature(desc, desc->Hq, Q, wq, wf, q_halo, qd, q_tail_out, stream);
+  if (st != LAWCAT_OK) return st;
+  st = lawcat_conv1d_feature(desc, desc->Hkv, K, wk, wf, k_halo, kd, k_tail_out, stream);
+  if (st != LAWCAT_OK) return st;
+  // the attention on the transformed q-dot, k-dot
+  return lawcat_gla_prefill(desc, qd, kd, V, gate_logits, S0, z0, O, den_out, S_out, z_out, inner, inner_bytes, stream);
 }
 
 int lawcat_layer_prefill_static(const lawcat_desc* desc, const void* Q, const void* K, const void* V,

@@ -207,4 +207,18 @@ hipError_t launch_conv1d(const ConvParams& p, hipStream_t stream) {
   return p.bf16 ? launch_typed<bf16_t>(p, stream) : launch_typed<float>(p, stream);
 }
 
+hipError_t launch_conv_tail(const ConvParams& p, hipStream_t stream) {
+  if (p.W <= 1 || p.tail_out == nullptr) return hipSuccess;
+  const int rowlen = p.H * p.d;
+  const long long total = (long long)p.B * (p.W - 1) * rowlen;
+  const unsigned grid = (unsigned)((total + 255) / 256);
+  if (p.bf16)
+    hipLaunchKernelGGL(conv_tail_kernel<bf16_t>, dim3(grid), dim3(256), 0, stream, (const bf16_t*)p.x,
+                       (const bf16_t*)p.halo, (bf16_t*)p.tail_out, p.B, p.T, rowlen, p.W);
+  else
+    hipLaunchKernelGGL(conv_tail_kernel<float>, dim3(grid), dim3(256), 0, stream, (const float*)p.x,
+                       (const float*)p.halo, (float*)p.tail_out, p.B, p.T, rowlen, p.W);
+  return hipGetLastError();
+}
+
 }  // namespace lawcat

@@ -21,6 +21,11 @@ struct ConvParams {
   int bf16;          // storage type
 };
 hipError_t launch_conv1d(const ConvParams& p, hipStream_t stream);
+// Copies the last W-1 raw rows of [halo ; x] (the conv cache) into p.tail_out without running the conv.
+hipError_t launch_conv_tail(const ConvParams& p, hipStream_t stream);
+// Conv followed by the shared linear layer with nonlinearity (section 4.1): y = phi(conv(x) Wf), Wf [H / group, d, d]
+// in the storage type; head h uses matrix h / group.  p.tail_out is not written (see launch_conv_tail).
+hipError_t launch_conv_feature(const ConvParams& p, const void* wf, int group, hipStream_t stream);
 
 struct RecurrentParams {
   const void* q;  // [B,T,Hq,d]  (q-dot)

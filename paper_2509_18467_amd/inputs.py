@@ -84,3 +84,14 @@ def make_inputs(wl: Workload, seed: int = 0, halo: bool = False, state: bool = F
         out["S0"] = normal((B, Hkv, d, d), 0.25)
         out["z0"] = np.abs(normal((B, Hkv, d), 2.0)) + f32(1.0)
     return out
+
+
+def make_feature_weights(wl: Workload, seed: int = 0) -> np.ndarray:
+    """wf [Hkv,d,d] for the shared linear layer of the feature map: the identity (where a converted model
+    starts) plus a dense N(0, 1/d) perturbation of the same energy, from a generator of its own so that the
+    tensors of make_inputs do not depend on it."""
+    rng = np.random.default_rng([seed, 0x5746])
+    wf = rng.standard_normal((wl.Hkv, wl.d, wl.d), dtype=np.float32)
+    wf *= np.float32(1.0 / np.sqrt(wl.d))
+    wf += np.eye(wl.d, dtype=np.float32)
+    return round_to_bf16(wf) if wl.dtype == "bf16" else wf

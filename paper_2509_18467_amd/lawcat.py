@@ -17,11 +17,12 @@ LIB_PATH = os.path.join(_HERE, "liblawcat.so")
 DTYPE_F32, DTYPE_BF16 = 0, 1
 PHI_IDENTITY, PHI_ELU1 = 0, 1
 CARRY_AUTO, CARRY_SEQUENTIAL, CARRY_TWO_LEVEL = 0, 1, 2
-CALL_CONV1D, CALL_GLA_PREFILL, CALL_GLA_STEP, CALL_LAYER_PREFILL = 0, 1, 2, 3
+CALL_CONV1D, CALL_GLA_PREFILL, CALL_GLA_STEP, CALL_LAYER_PREFILL, CALL_LAYER_PREFILL_FM = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gla_prefill", "lawcat_gla_step", "lawcat_gla_steps",
-    "lawcat_layer_prefill", "lawcat_layer_prefill_static", "lawcat_layer_prefill_timed", "lawcat_status_string", "lawcat_version",
+    "lawcat_conv1d_feature", "lawcat_layer_prefill", "lawcat_layer_prefill_fm", "lawcat_layer_prefill_static",
+    "lawcat_layer_prefill_timed", "lawcat_status_string", "lawcat_version",
 )
 
 
@@ -72,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.lawcat_status_string.argtypes = [ci]
         L.lawcat_status_string.restype = ctypes.c_char_p
         L.lawcat_version.restype = ci
+        L.lawcat_conv1d_feature.argtypes = [dp, ci] + [vp] * 7
+        L.lawcat_conv1d_feature.restype = ci
+        L.lawcat_layer_prefill_fm.argtypes = [dp] + [vp] * 18 + [sz, vp]
+        L.lawcat_layer_prefill_fm.restype = ci
         L.lawcat_layer_prefill_static.argtypes = [dp] + [vp] * 16 + [vp]
         L.lawcat_layer_prefill_static.restype = ci
         L.lawcat_layer_prefill_timed.argtypes = [dp] + [vp] * 17 + [sz, vp, vp, vp]
@@ -142,6 +147,20 @@ def layer_prefill(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O,
                                       _p(S0), _p(z0), _p(q_halo), _p(k_halo), _p(O), _p(den_out), _p(S_out),
                                       _p(z_out), _p(q_tail_out), _p(k_tail_out), _p(workspace), nbytes,
                                       _stream(stream)))
+
+
+def conv1d_feature(desc, n_heads, x, w, wf, halo, y, tail_out, stream=None):
+    _check(lib().lawcat_conv1d_feature(ctypes.byref(desc), n_heads, _p(x), _p(w), _p(wf), _p(halo), _p(y),
+                                       _p(tail_out), _stream(stream)))
+
+
+def layer_prefill_fm(desc, Q, K, V, gate_logits, wq, wk, wf, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,
+                     q_tail_out, k_tail_out, workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lawcat_layer_prefill_fm(ctypes.byref(desc), _p(Q), _p(K), _p(V), _p(gate_logits), _p(wq), _p(wk),
+                                         _p(wf), _p(S0), _p(z0), _p(q_halo), _p(k_halo), _p(O), _p(den_out),
+                                         _p(S_out), _p(z_out), _p(q_tail_out), _p(k_tail_out), _p(workspace), nbytes,
+                                         _stream(stream)))
 
 
 STATIC_WORKSPACE_BYTES = 24 << 20

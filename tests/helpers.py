@@ -80,8 +80,9 @@ def desc_for(wl: Workload, **kw):
                             dtype=lawcat.DTYPE_BF16 if wl.dtype == "bf16" else lawcat.DTYPE_F32, **kw)
 
 
-def run_layer_prefill(wl: Workload, x: dict, feature_map=1, den=True, tails=True, **desc_kw):
-    """Upload x (numpy float32 dict from make_inputs), call lawcat_layer_prefill, return numpy float64 results."""
+def run_layer_prefill(wl: Workload, x: dict, feature_map=1, den=True, tails=True, wf=None, **desc_kw):
+    """Upload x (numpy float32 dict from make_inputs), call lawcat_layer_prefill (lawcat_layer_prefill_fm if the
+    shared feature matrix wf is given), return numpy float64 results."""
     dt = tdtype(wl)
     d = desc_for(wl, feature_map=feature_map, **desc_kw)
     Q, K, V, G, wq, wk = (dev(x[n], dt) for n in ("Q", "K", "V", "G", "wq", "wk"))
@@ -93,15 +94,37 @@ def run_layer_prefill(wl: Workload, x: dict, feature_map=1, den=True, tails=True
     z = torch.empty(wl.B, wl.Hkv, wl.d, dtype=torch.float32, device="cuda")
     qt = torch.empty(wl.B, wl.W - 1, wl.Hq, wl.d, dtype=dt, device="cuda") if tails and wl.W > 1 else None
     kt = torch.empty(wl.B, wl.W - 1, wl.Hkv, wl.d, dtype=dt, device="cuda") if tails and wl.W > 1 else None
-    ws = lawcat.alloc_workspace(d, lawcat.CALL_LAYER_PREFILL)
-    lawcat.layer_prefill(d, Q, K, V, G, wq, wk, S0, z0, qh, kh, O, den_out, S, z, qt, kt, ws)
+    if wf is None:
+        ws = lawcat.alloc_workspace(d, lawcat.CALL_LAYER_PREFILL)
+        lawcat.layer_prefill(d, Q, K, V, G, wq, wk, S0, z0, qh, kh, O, den_out, S, z, qt, kt, ws)
+    else:
+        ws = lawcat.alloc_workspace(d, lawcat.CALL_LAYER_PREFILL_FM)
+        lawcat.layer_prefill_fm(d, Q, K, V, G, wq, wk, dev(wf, dt), S0, z0, qh, kh, O, den_out, S, z, qt, kt, ws)
     torch.cuda.synchronize()
     r = {"o": host(O), "S": host(S), "z": host(z)}
     if den:
         r["den"] = host(den_out)
     if qt is not None:
         r["q_tail"], r["k_tail"] = host(qt), host(kt)
+    if wf is not None:
+        # q-dot and k-dot as the call staged them: the head of the workspace, k-dot at the next multiple of 256 bytes
+        nq, nk = wl.B * wl.T * wl.Hq * wl.d, wl.B * wl.T * wl.Hkv * wl.d
+        off = -(-nq * Q.element_size() // 256) * 256
+        r["q_dot"] = host(ws[:nq * Q.element_size()].view(dt).reshape(wl.B, wl.T, wl.Hq, wl.d))
+        r["k_dot"] = host(ws[off:off + nk * Q.element_size()].view(dt).reshape(wl.B, wl.T, wl.Hkv, wl.d))
     return r
+
+
+def run_conv_feature(wl: Workload, x, w, wf, halo=None, feature_map=1):
+    dt = tdtype(wl)
+    H = x.shape[2]
+    d = desc_for(wl, feature_map=feature_map)
+    xd, wd, fd, hd = dev(x, dt), dev(w, dt), dev(wf, dt), dev(halo, dt)
+    y = torch.empty_like(xd)
+    tail = torch.empty(wl.B, wl.W - 1, H, wl.d, dtype=dt, device="cuda") if wl.W > 1 else None
+    lawcat.conv1d_feature(d, H, xd, wd, fd, hd, y, tail)
+    torch.cuda.synchronize()
+    return host(y), (host(tail) if tail is not None else None)
 
 
 def run_gla_prefill(wl: Workload, q, k, v, g, S0=None, z0=None, **desc_kw):

@@ -163,3 +163,35 @@ def test_static_entry_point_rejects_what_its_buffer_cannot_hold():
     assert "static buffer" in lawcat.status_string(-7)
     text = open(os.path.join(ROOT, "include", "lawcat.h")).read()
     assert int(re.search(r"LAWCAT_STATIC_WORKSPACE_BYTES \((\d+)u << 20\)", text).group(1)) << 20 == lawcat.STATIC_WORKSPACE_BYTES
+
+
+def test_feature_map_entry_points_check_their_arguments():
+    """lawcat_conv1d_feature and lawcat_layer_prefill_fm: shared matrix required, head count a multiple of Hkv,
+    workspace = staged q-dot and k-dot plus what lawcat_gla_prefill needs."""
+    L = lawcat.lib()
+    d = lawcat.make_desc(1, 4096, 32, 8, 64)
+
+    def feat(desc, n_heads, wf=A, x=A):
+        return L.lawcat_conv1d_feature(ctypes.byref(desc), n_heads, x, A, wf, None, A, None, None)
+
+    assert feat(d, 32, wf=None) == -1
+    assert feat(d, 12) == -2                      # 12 query heads cannot share 8 matrices evenly
+    assert feat(d, 0) == -2
+    assert feat(d, 8, x=ctypes.c_void_p(0x1004)) == -5
+    assert feat(lawcat.make_desc(1, 16, 4, 2, 96), 4) == -3
+
+    need = lawcat.workspace_bytes(d, lawcat.CALL_LAYER_PREFILL_FM)
+    staged = 4096 * (32 + 8) * 64 * 2
+    assert need >= staged + lawcat.workspace_bytes(d, lawcat.CALL_GLA_PREFILL)
+    assert need < staged + lawcat.workspace_bytes(d, lawcat.CALL_GLA_PREFILL) + 3 * 256
+    f32 = lawcat.make_desc(1, 512, 4, 2, 64, dtype=0)
+    assert lawcat.workspace_bytes(f32, lawcat.CALL_LAYER_PREFILL_FM) >= 512 * 6 * 64 * 4
+
+    def layer(desc, ws, nbytes, wf=A):
+        return L.lawcat_layer_prefill_fm(ctypes.byref(desc), A, A, A, A, A, A, wf, None, None, None, None, A, None,
+                                         A, A, None, None, ws, nbytes, None)
+
+    assert layer(d, A, need, wf=None) == -1
+    assert layer(d, A, need - 1) == -4
+    assert layer(d, None, 0) == -4
+    assert layer(lawcat.make_desc(1, 0, 4, 2, 64), A, need) == -2

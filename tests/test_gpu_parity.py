@@ -9,7 +9,7 @@ import pytest
 import torch
 
 from paper_2509_18467_amd import lawcat
-from paper_2509_18467_amd.inputs import WORKLOADS, Workload, make_inputs, round_to_bf16
+from paper_2509_18467_amd.inputs import WORKLOADS, Workload, make_feature_weights, make_inputs, round_to_bf16
 
 import helpers as H
 
@@ -43,6 +43,35 @@ def test_conv1d_causal(oracle, dtype, T, Hh, d, W, phi, halo):
     y, tail = H.run_conv(wl, x, w, hl, phi)
     ref = oracle.conv1d_causal(x, w, hl, phi)
     H.assert_close(y, ref, wl, "conv y")
+    if W > 1:
+        full = np.concatenate([np.zeros((wl.B, W - 1, Hh, d)) if hl is None else hl, x], axis=1)
+        assert np.array_equal(tail, full[:, -(W - 1):]), "tail rows must be bit-exact copies"
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("T,Hh,Hkv,d,W,phi,halo", [
+    (256, 2, 2, 64, 4, 1, False), (37, 4, 2, 64, 4, 0, True), (1, 8, 2, 128, 4, 1, True), (300, 8, 8, 128, 4, 0, True),
+    (1000, 4, 1, 128, 2, 1, False), (129, 2, 2, 64, 1, 1, False), (530, 32, 8, 64, 3, 0, True), (257, 6, 3, 64, 4, 1, True),
+])
+def test_conv1d_feature(oracle, dtype, T, Hh, Hkv, d, W, phi, halo):
+    """The shared linear layer after the conv (section 4.1): n_heads = Hkv (keys) and n_heads = a multiple (queries)."""
+    wl = Workload("convf", 2, T, Hh, Hkv, d, W, dtype)
+    _say("conv + linear feature map", wl, phi, halo)
+    rng = np.random.default_rng(T + d)
+    x = _store(wl, rng.standard_normal((wl.B, T, Hh, d)) * 0.5)
+    w = _store(wl, rng.standard_normal((Hh, d, W)) * 0.5)
+    hl = _store(wl, rng.standard_normal((wl.B, W - 1, Hh, d)) * 0.5) if (halo and W > 1) else None
+    wf = make_feature_weights(wl, seed=T)
+    y, tail = H.run_conv_feature(wl, x, w, wf, hl, phi)
+    xc = oracle.conv1d_causal(x, w, hl, 0)
+    ref = oracle.feature_linear(xc, wf, phi)
+    if phi == 1:
+        r = H.assert_close(y, ref, wl, "conv + feature y")
+    else:
+        # signed features reach 4-5 sigma, where the bf16 half-ulp of the stored result alone is 1.5e-2 of RMS:
+        # the bar adds one half-ulp of the sum of the absolute values of the products
+        r = H.assert_close(y, ref, wl, "conv + feature y", 1, oracle.feature_linear(np.abs(xc), np.abs(wf), 0))
+    _say("  error / bar", f"{r:.3f}")
     if W > 1:
         full = np.concatenate([np.zeros((wl.B, W - 1, Hh, d)) if hl is None else hl, x], axis=1)
         assert np.array_equal(tail, full[:, -(W - 1):]), "tail rows must be bit-exact copies"
@@ -284,6 +313,43 @@ def test_layer_prefill_full_size(oracle, name, phi):
     got = H.run_layer_prefill(wl, x, feature_map=phi)
     ref = oracle.layer_prefill(x["Q"], x["K"], x["V"], x["G"], x["wq"], x["wk"], phi)
     _check_prefill(got, ref, wl, phi, f"layer_prefill[{wl.name},phi={phi}]", terms=_layer_terms(oracle, ref, x, phi))
+
+
+# ------------------------------------------------------------------ the feature map with its shared linear layer
+@pytest.mark.parametrize("name,T,phi,extras", [
+    ("tiny", None, 1, False), ("tiny", 203, 0, True), ("llama1b_8k", 777, 1, True), ("mistral7b_16k", 333, 0, True),
+    ("llama1b_8k", None, 1, False), ("llama1b_8k", None, 0, False),
+    ("mistral7b_16k", None, 1, False), ("mistral7b_16k", None, 0, False),
+])
+def test_layer_prefill_with_linear_feature_map(oracle, name, T, phi, extras):
+    """q-dot = phi(conv(Q) Wf), k-dot = phi(conv(K) Wf) (section 4.1), then the attention: lawcat_layer_prefill_fm.
+
+    With 1 + ELU the whole call is held to the bar of the fused layer, end to end against the fp64 oracle.  With
+    signed features (identity phi: not a configuration of the paper, whose layer has a nonlinearity) the
+    numerator is a sum of cancelling terms, and the bf16 rounding of the staged q-dot and k-dot moves it by more
+    than the 2e-2 bar leaves; there the two stages are held to their bars one after the other: the staged
+    features against the oracle's, then the attention against the oracle run on the staged features (which is
+    how lawcat_conv1d_causal followed by lawcat_gla_prefill is tested)."""
+    wl = WORKLOADS[name] if T is None else WORKLOADS[name].with_T(T)
+    x = make_inputs(wl, seed=0, halo=extras, state=extras)
+    wf = make_feature_weights(wl, seed=0)
+    _say("layer_prefill_fm", wl, "phi", phi, "extras", extras)
+    got = H.run_layer_prefill(wl, x, feature_map=phi, wf=wf)
+    ref = oracle.layer_prefill(x["Q"], x["K"], x["V"], x["G"], x["wq"], x["wk"], phi, 1.0, 0.0,
+                               x.get("S0"), x.get("z0"), x.get("q_halo"), x.get("k_halo"), wf=wf)
+    tag = f"layer_prefill_fm[{wl.name},phi={phi}]"
+    if phi == 0:
+        for name, raw, w, hl in (("q_dot", "Q", "wq", "q_halo"), ("k_dot", "K", "wk", "k_halo")):
+            xc = oracle.conv1d_causal(x[raw], x[w], x.get(hl), 0)
+            r = H.assert_close(got[name], ref[name], wl, f"{tag} staged {name}", 1,
+                               oracle.feature_linear(np.abs(xc), np.abs(wf), 0))
+            _say(f"  staged {name}: error / bar {r:.3f}")
+        ref2 = oracle.gla_prefill(got["q_dot"], got["k_dot"], x["V"], x["G"], 1.0, 0.0, x.get("S0"), x.get("z0"))
+        terms = _abs_terms(oracle, got["q_dot"], got["k_dot"], x["V"], x["G"], 1.0, x.get("S0"), x.get("z0"))
+        _check_prefill(got, ref2, wl, phi, tag + " attention on the staged features", terms=terms)
+    else:
+        _check_prefill(got, ref, wl, phi, tag)
+    assert np.array_equal(got["q_tail"], ref["q_tail"]) and np.array_equal(got["k_tail"], ref["k_tail"])
 
 
 # ------------------------------------------------------------------ continuation (conv cache + state)
