@@ -159,6 +159,37 @@ def run_side_ops(wl, steps=30):
     torch.cuda.synchronize()
     conv_ms = e0.elapsed_time(e1) / steps
     conv_bytes = 2 * xs[0].numel() * xs[0].element_size()
+    # the same conv followed by the shared d x d matrix of the feature map (section 4.1), one kernel
+    wf = (torch.eye(wl.d, device="cuda") + torch.randn(wl.Hkv, wl.d, wl.d, device="cuda") * wl.d ** -0.5).to(dt)
+    for i in range(3):
+        lawcat.conv1d_feature(desc, wl.Hq, xs[i % nset], w, wf, None, ys[i % nset], None)
+    e0.record()
+    for i in range(steps):
+        lawcat.conv1d_feature(desc, wl.Hq, xs[i % nset], w, wf, None, ys[i % nset], None)
+    e1.record()
+    torch.cuda.synchronize()
+    feat_ms = e0.elapsed_time(e1) / steps
+    # and the whole layer with that feature map: conv + matrix on Q and on K, staged, then the attention
+    wk = (0.5 * torch.randn(wl.Hkv, wl.d, wl.W, device="cuda")).to(dt)
+    Ks, Vs, Gs = ([torch.randn(wl.B, wl.T, wl.Hkv, wl.d, device="cuda").mul_(sc).to(dt) for _ in range(nset)]
+                  for sc in (0.125, 0.125, 1.0))
+    Sf = torch.empty(wl.B, wl.Hkv, wl.d, wl.d, device="cuda")
+    zf = torch.empty(wl.B, wl.Hkv, wl.d, device="cuda")
+    wsf = lawcat.alloc_workspace(desc, lawcat.CALL_LAYER_PREFILL_FM)
+
+    def fm_layer(i):
+        j = i % nset
+        lawcat.layer_prefill_fm(desc, xs[j], Ks[j], Vs[j], Gs[j], w, wk, wf, None, None, None, None, ys[j], None, Sf, zf,
+                                None, None, wsf)
+
+    for i in range(3):
+        fm_layer(i)
+    e0.record()
+    for i in range(steps):
+        fm_layer(i)
+    e1.record()
+    torch.cuda.synchronize()
+    fm_layer_ms = e0.elapsed_time(e1) / steps
     # decode step
     d1 = lawcat.make_desc(wl.B, 1, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W, dtype=lawcat.DTYPE_BF16, feature_map=1)
     q = torch.rand(wl.B, wl.Hq, wl.d, device="cuda").to(dt) + 0.5
@@ -196,6 +227,10 @@ def run_side_ops(wl, steps=30):
     return {"gla_steps_block256": {"us_per_step": block_us},
             "conv1d_causal_q": {"ms": conv_ms, "GB/s": conv_bytes / (conv_ms * 1e-3) / 1e9,
                                 "frac_of_hbm_peak": conv_bytes / (conv_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "conv1d_feature_q": {"ms": feat_ms, "GB/s": conv_bytes / (feat_ms * 1e-3) / 1e9,
+                                 "frac_of_hbm_peak": conv_bytes / (feat_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                 "mfma_TFLOP/s": 2 * xs[0].numel() * wl.d / (feat_ms * 1e-3) / 1e12},
+            "layer_prefill_fm": {"ms": fm_layer_ms, "tokens_per_s": wl.B * wl.T / (fm_layer_ms * 1e-3)},
             "gla_step": {"us_per_step": step_us, "state_bytes_per_step": 2 * S.numel() * 4}}
 
 
