@@ -68,6 +68,7 @@ struct ChunkArgs {
   float* z_out;
   bf16_t *q_tail, *k_tail;
   float* ws;
+  int* seg_live;   // [B*Hkv][nseg]: written by the state pass, 0 = the segment's total decay is exactly zero in every channel
   int B, T, Hq, Hkv, W;
   int group;   // query heads per kv head (Hq / Hkv)
   int qh0;     // first query head, within its group, that this launch of the output pass covers
@@ -456,6 +457,14 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
   const int c0 = 64 * (w % G::CH) + 2 * cp;        // first of the two channels
   const int tl0 = kChunk * mcw + 8 * th;           // first token of the patch within the granule
 
+  // Output pass: did the scan run for this head?  It leaves the workspace untouched when no segment of the head
+  // passes anything on (every total decay exactly zero): then a segment starts from its predecessor's
+  // contribution as the state pass wrote it, the first from S0, z0.  The loads are issued here and reduced after
+  // the conv weights below, so that the two latencies overlap.
+  int live_any = 0;
+  if (OUTPUT && a.nseg > 1)
+    for (int j = tid; j < a.nseg - 1; j += G::TEAM) live_any |= a.seg_live[(size_t)bh * a.nseg + j];
+
   float* wl = reinterpret_cast<float*>(smem + G::kWl);
   if (CONV) {
     // conv weights as fp32 [head][channel][4 taps], taps beyond W zero; row GR is the key head
@@ -496,13 +505,25 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
     const float* Sin = nullptr;
     const float* zin = nullptr;
     if (OUTPUT && active) {
+      bool scanned = false;
       if (a.nseg > 1) {
-        Sin = a.ws + ((size_t)bh * a.nseg + seg) * G::kSlot;
-        zin = Sin + D * D;
-      } else if (a.S0 != nullptr) {
-        Sin = a.S0 + (size_t)bh * D * D;
+        // team-wide OR through the per-wave flag words (free until the granule loop; the barrier that ends the
+        // prologue separates these reads from the loop's first writes)
+        const bool wave_any = __builtin_amdgcn_ballot_w64(live_any != 0) != 0;
+        if (l == 0) *reinterpret_cast<int*>(smem + G::kFl + w * 4) = wave_any ? 1 : 0;
+        __syncthreads();
+        int any = 0;
+#pragma unroll
+        for (int j = 0; j < G::NW; ++j) any |= *reinterpret_cast<const int*>(smem + G::kFl + j * 4);
+        scanned = __builtin_amdgcn_readfirstlane(any) != 0;
       }
-      if (a.nseg == 1 && a.z0 != nullptr) zin = a.z0 + (size_t)bh * D;
+      if (scanned || (a.nseg > 1 && seg > 0)) {
+        Sin = a.ws + ((size_t)bh * a.nseg + (scanned ? seg : seg - 1)) * G::kSlot;
+        zin = Sin + D * D;
+      } else {
+        if (a.S0 != nullptr) Sin = a.S0 + (size_t)bh * D * D;
+        if (a.z0 != nullptr) zin = a.z0 + (size_t)bh * D;
+      }
     }
 #pragma unroll
     for (int rt = 0; rt < G::RT; ++rt) {
@@ -534,6 +555,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
   __syncthreads();  // conv weights are in LDS
 
   // Per granule: compute stage, barrier, MFMA stage, barrier.
+  bool dead = false;   // state pass: after the last granule walked, the segment's total decay is exactly zero
 #pragma unroll 1
   for (int gi = 0; gi < nseg_gran; ++gi) {
     const int t0 = tfirst + gi * tstep;
@@ -567,7 +589,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
         if (l == 0) *reinterpret_cast<int*>(smem + G::kFl + w * 4) = alive ? 1 : 0;
       }
       __syncthreads();
-      bool dead = false;
+      dead = false;
       if (!OUTPUT) {
         int any = 0;
 #pragma unroll
@@ -795,6 +817,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
       }
     // total decay of the segment: the waves that loaded chunk 0 hold it for their two channels
     if (ddst != nullptr && mcw == 0 && th == 0) *reinterpret_cast<float2*>(ddst + c0) = make_float2(rgran[0], rgran[1]);
+    if (!OUTPUT && tid == 0) a.seg_live[(size_t)bh * a.nseg + seg] = dead ? 0 : 1;
   }
   // ---- conv cache out: the last W-1 raw rows of [halo ; x] for this workgroup's heads
   if (OUTPUT && CONV && seg == a.nseg - 1 && a.W > 1) {
@@ -823,8 +846,9 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
 // combined through LDS, and each thread replays its group from its true start.  All loads of a
 // group are independent of the running state and issued together.
 template <int D>
-__global__ void __launch_bounds__(256) segment_scan_kernel(float* __restrict__ ws, const float* __restrict__ S0,
-                                                          const float* __restrict__ z0, int nseg) {
+__global__ void __launch_bounds__(256) segment_scan_kernel(float* __restrict__ ws, const int* __restrict__ seg_live,
+                                                          const float* __restrict__ S0, const float* __restrict__ z0,
+                                                          int nseg) {
   constexpr int kSlot = D * D + 2 * D;
   constexpr int NG = 8, U = 8;
   __shared__ float agg_a[NG][32], agg_x[NG][32];
@@ -832,6 +856,14 @@ __global__ void __launch_bounds__(256) segment_scan_kernel(float* __restrict__ w
   const int e = blockIdx.x * 32 + el;
   const bool live = e < D * D + D;
   const int bh = blockIdx.y;
+  {
+    // No segment of this head passes anything on (every total decay is exactly zero: the usual case with gate
+    // logits ~ N(0,1) and segments of hundreds of tokens): each start state is the predecessor's contribution,
+    // which the output pass reads where it lies.  Nothing to do, and nothing is written.
+    int any = 0;
+    for (int j = threadIdx.x; j < nseg - 1; j += 256) any |= seg_live[(size_t)bh * nseg + j];
+    if (__syncthreads_or(any) == 0) return;
+  }
   const int c = !live ? 0 : (e < D * D ? e / D : e - D * D);
   const int ec = live ? e : 0;
   float* slot = ws + (size_t)bh * nseg * kSlot;
@@ -914,8 +946,8 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream, bool with_state_pa
     hipLaunchKernelGGL(k1, dim3(a.nseg - 1, heads), dim3(G::TEAM), lds1, stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(segment_scan_kernel<D>, dim3((D * D + D + 31) / 32, heads), dim3(256), 0, stream, a.ws, a.S0,
-                       a.z0, a.nseg);
+    hipLaunchKernelGGL(segment_scan_kernel<D>, dim3((D * D + D + 31) / 32, heads), dim3(256), 0, stream, a.ws, a.seg_live,
+                       a.S0, a.z0, a.nseg);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
