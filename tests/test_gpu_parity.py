@@ -257,6 +257,29 @@ def test_gates_mixed_with_saturated_logits(oracle, d, phi):
 
 
 @pytest.mark.parametrize("d", [64, 128])
+def test_memory_carried_across_some_segments_only(oracle, d):
+    """Segments of 128 tokens, N(0,1) gates (no segment passes anything on: the scan has nothing to do and the
+    output pass starts from its predecessor's contribution) except that kv head 1 holds one channel in eight
+    open from token 300 to 700, across three segment boundaries (those segments pass their state on, the scan
+    runs for that head), and head 0 does so in the last two segments only.  A start state comes in as well.
+    The open channels pile up hundreds of undecayed terms while the rest of the state stays small, so one RMS
+    over the tensor says little about them: the bar is the forward-error one (half a bf16 ulp of the sum of the
+    absolute values of the terms, on top of 2e-2 of RMS), as for signed features."""
+    wl = Workload(f"carry_some_d{d}", 2, 1100, 8, 2, d, 4, "bf16")
+    x = make_inputs(wl, seed=33, state=True)
+    x["G"][:, 300:700, 1, ::8] = 30.0
+    x["G"][0, 850:, 0, 3::8] = 30.0
+    x["G"] = round_to_bf16(x["G"])
+    _say("carry across some segments", wl)
+    got = H.run_layer_prefill(wl, x, feature_map=1, segment=128)
+    ref = oracle.layer_prefill(x["Q"], x["K"], x["V"], x["G"], x["wq"], x["wk"], 1, 1.0, 0.0, x["S0"], x["z0"])
+    terms = _abs_terms(oracle, ref["q_dot"], ref["k_dot"], x["V"], x["G"], 1.0, x["S0"], x["z0"])
+    _check_prefill(got, ref, wl, 1, f"carry across some segments d={d}", split=True, terms=terms)
+    for k in ("o", "den"):
+        H.assert_close(got[k], ref[k], wl, f"carry across some segments {k}")
+
+
+@pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("gate_scale", [0.0, 4.0, 16.0])
 def test_gate_scale_extremes(oracle, d, gate_scale):
     """gate_scale = 0 switches the decay off (alpha = 1: checked like the open gates); 4 and 16 push most steps
