@@ -256,12 +256,13 @@ def mfma_flops_per_token(wl, chunk=16) -> int:
     return wl.Hq * (2 * chunk * d + 2 * chunk * d + 2 * d * d) + wl.Hkv * 2 * d * d
 
 
-def read_traffic(name):
-    """HBM bytes per output-pass launch from the committed rocprofv3 --pmc summary, if present."""
+def read_traffic(name, key="traffic_bytes_per_launch"):
+    """HBM bytes per output-pass launch (or, key="whole_step_traffic_bytes", per step: state pass + scan + output
+    pass) from the committed rocprofv3 --pmc summary of this workload, if present."""
     path = os.path.join(ROOT, "profiles", f"output_pass_{name}_hbm_traffic.txt")
     if os.path.exists(path):
         for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
+            if line.startswith(key + ":"):
                 return int(line.split(":")[1])
     return None
 
@@ -269,8 +270,8 @@ def read_traffic(name):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50, help="untimed steps first (they also bring the clocks up)")
     ap.add_argument("--workload", default="llama1b_32k")
     ap.add_argument("--feature-map", type=int, default=1)
     ap.add_argument("--quick", action="store_true",
@@ -325,7 +326,8 @@ def main():
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                            "traffic": read_traffic(wl.name), "kernel_ms": r["kernel_ms"],
                            "algorithmic_bytes_per_launch": r["bytes_step"],
-                           "whole_step_frac": r["bytes_step"] / (r["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                           "whole_step_frac": r["bytes_step"] / (r["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                           "whole_step_traffic": read_traffic(wl.name, "whole_step_traffic_bytes")}
     flops = mfma_flops_per_token(wl) * wl.B * wl.T
     out["mfma"] = {"useful_flops_per_token": mfma_flops_per_token(wl), "achieved_tflops": flops / (r["ms_per_step"] * 1e-3) / 1e12,
                    "frac_of_bf16_peak": flops / (r["ms_per_step"] * 1e-3) / 2.5e15}
@@ -340,7 +342,7 @@ def main():
         # the rest of the metric's range (T = 8K .. 128K, both layer shapes) and the other axes of the headline
         # shape, device-generated inputs of the same distributions, fewer steps each
         sweep = {}
-        st, wu = max(5, args.steps // 2), max(2, args.warmup // 2)
+        st, wu = max(5, args.steps // 4), max(2, args.warmup // 4)
         for name in ("llama1b_8k", "llama1b_32k", "mistral7b_16k", "mistral7b_128k"):
             if name == wl.name and args.feature_map == 1 and args.gate_scale == 1.0:
                 continue
