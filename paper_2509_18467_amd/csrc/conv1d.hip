@@ -9,7 +9,6 @@
 namespace lawcat {
 namespace {
 
-constexpr int kStrip = 64;  // tokens per thread
 constexpr int kGroup = 4;   // rows fetched together, one group ahead of the arithmetic
 
 template <typename T> struct Io;
@@ -68,7 +67,8 @@ __device__ inline float apply_phi(float x, int phi) {
   return x;
 }
 
-template <typename T>
+// kStrip: tokens per thread (64; 32 or 16 where longer strips would leave compute units without a workgroup)
+template <typename T, int kStrip>
 __global__ void __launch_bounds__(256) conv1d_causal_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                             const T* __restrict__ halo, T* __restrict__ y,
                                                             int B, int Tn, int rowlen, int W, int phi) {
@@ -184,12 +184,19 @@ template <typename T>
 hipError_t launch_typed(const ConvParams& p, hipStream_t stream) {
   const int rowlen = p.H * p.d;
   const int vecs = rowlen / Io<T>::VEC;
-  const long long nstrips = (p.T + kStrip - 1) / kStrip;
-  const long long threads = (long long)p.B * nstrips * vecs;
   const int block = 256;
-  const long long grid = (threads + block - 1) / block;
-  hipLaunchKernelGGL(conv1d_causal_kernel<T>, dim3((unsigned)grid), dim3(block), 0, stream, (const T*)p.x,
-                     (const T*)p.w, (const T*)p.halo, (T*)p.y, p.B, p.T, rowlen, p.W, p.phi);
+  auto blocks = [&](int strip) { return ((long long)p.B * ((p.T + strip - 1) / strip) * vecs + block - 1) / block; };
+  // 64-token strips unless that leaves fewer than two workgroups per compute unit (few heads, short sequences)
+  constexpr long long kWant = 512;
+  if (blocks(64) >= kWant)
+    hipLaunchKernelGGL((conv1d_causal_kernel<T, 64>), dim3((unsigned)blocks(64)), dim3(block), 0, stream, (const T*)p.x,
+                       (const T*)p.w, (const T*)p.halo, (T*)p.y, p.B, p.T, rowlen, p.W, p.phi);
+  else if (blocks(32) >= kWant)
+    hipLaunchKernelGGL((conv1d_causal_kernel<T, 32>), dim3((unsigned)blocks(32)), dim3(block), 0, stream, (const T*)p.x,
+                       (const T*)p.w, (const T*)p.halo, (T*)p.y, p.B, p.T, rowlen, p.W, p.phi);
+  else
+    hipLaunchKernelGGL((conv1d_causal_kernel<T, 16>), dim3((unsigned)blocks(16)), dim3(block), 0, stream, (const T*)p.x,
+                       (const T*)p.w, (const T*)p.halo, (T*)p.y, p.B, p.T, rowlen, p.W, p.phi);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (p.tail_out != nullptr && p.W > 1) {
