@@ -157,6 +157,27 @@ LAWCAT_API int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, cons
                          void* k_tail_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * lawcat_layer_prefill for sequences of different lengths packed back to back (continuous batching, chunked
+ * prefill of several requests): section 4.2's recurrence restarts at every sequence boundary, and section 4.1's
+ * conv does not reach across it.  desc->B = number of sequences, desc->T = an upper bound of their lengths.
+ *   seq_start  HOST array of B + 1 token offsets, seq_start[0] = 0, strictly increasing: sequence i owns
+ *              tokens seq_start[i] .. seq_start[i+1] - 1; total = seq_start[B]
+ *   Q, O [total,Hq,dk]   K, V, gate_logits [total,Hkv,dk]   den_out [total,Hq] (nullable)
+ *   S0, z0, S_out, z_out, q_halo, k_halo, q_tail_out, k_tail_out: per sequence, shaped as in
+ *   lawcat_layer_prefill with B sequences (chunked prefill: feed a sequence's S_out, z_out and tails back in).
+ * One lawcat_layer_prefill with B = 1 per sequence, enqueued in order on `stream`; they share `workspace`,
+ * which must cover lawcat_workspace_bytes(desc_i, LAWCAT_CALL_LAYER_PREFILL) for desc_i = desc with B = 1 and
+ * T = each length.  All sequences are checked before anything is enqueued: a length below 1 or above desc->T
+ * is LAWCAT_E_BAD_DESC.
+ */
+LAWCAT_API int lawcat_layer_prefill_varlen(const lawcat_desc* desc, const int32_t* seq_start, const void* Q,
+                                const void* K, const void* V, const void* gate_logits, const void* wq,
+                                const void* wk, const float* S0, const float* z0, const void* q_halo,
+                                const void* k_halo, void* O, float* den_out, float* S_out, float* z_out,
+                                void* q_tail_out, void* k_tail_out, void* workspace, size_t workspace_bytes,
+                                void* stream);
+
+/*
  * The layer of Fig. 1 with the feature map of section 4.1 in full: after the conv, "a linear layer with
  * nonlinearity", the same for the query and the key,
  *   q-dot = phi( conv(Q) Wf ),  k-dot = phi( conv(K) Wf ),

@@ -217,13 +217,16 @@ int layer_prefill_impl(const lawcat_desc* desc, const void* Q, const void* K, co
                        const void* gate_logits, const void* wq, const void* wk, const float* S0,
                        const float* z0, const void* q_halo, const void* k_halo, void* O, float* den_out,
                        float* S_out, float* z_out, void* q_tail_out, void* k_tail_out, void* workspace,
-                       size_t workspace_bytes, void* stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                       size_t workspace_bytes, void* stream, hipEvent_t ev_start, hipEvent_t ev_stop,
+                       bool den_rows_packed = false) {
   int st = check_desc(desc, true);
   if (st != LAWCAT_OK) return st;
   if (!Q || !K || !V || !gate_logits || !wq || !wk || !O || !S_out || !z_out) return LAWCAT_E_NULL;
+  // den_out is written one float at a time; a sequence inside a packed batch may start at any row of it
+  const bool den_ok = den_rows_packed ? (reinterpret_cast<uintptr_t>(den_out) % sizeof(float) == 0) : aligned16(den_out);
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(gate_logits) || !aligned16(wq) ||
       !aligned16(wk) || !aligned16(S0) || !aligned16(z0) || !aligned16(q_halo) || !aligned16(k_halo) ||
-      !aligned16(O) || !aligned16(den_out) || !aligned16(S_out) || !aligned16(z_out) ||
+      !aligned16(O) || !den_ok || !aligned16(S_out) || !aligned16(z_out) ||
       !aligned16(q_tail_out) || !aligned16(k_tail_out) || !aligned16(workspace))
     return LAWCAT_E_ALIGN;
   const size_t need = workspace_bytes_checked(desc, LAWCAT_CALL_LAYER_PREFILL);
@@ -278,6 +281,50 @@ int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, 
                          size_t workspace_bytes, void* stream) {
   return layer_prefill_impl(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,
                             q_tail_out, k_tail_out, workspace, workspace_bytes, stream, nullptr, nullptr);
+}
+
+int lawcat_layer_prefill_varlen(const lawcat_desc* desc, const int32_t* seq_start, const void* Q, const void* K,
+                                const void* V, const void* gate_logits, const void* wq, const void* wk,
+                                const float* S0, const float* z0, const void* q_halo, const void* k_halo, void* O,
+                                float* den_out, float* S_out, float* z_out, void* q_tail_out, void* k_tail_out,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (seq_start == nullptr || !Q || !K || !V || !gate_logits || !wq || !wk || !O || !S_out || !z_out) return LAWCAT_E_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(gate_logits) || !aligned16(wq) ||
+      !aligned16(wk) || !aligned16(S0) || !aligned16(z0) || !aligned16(q_halo) || !aligned16(k_halo) ||
+      !aligned16(O) || !aligned16(den_out) || !aligned16(S_out) || !aligned16(z_out) ||
+      !aligned16(q_tail_out) || !aligned16(k_tail_out) || !aligned16(workspace))
+    return LAWCAT_E_ALIGN;
+  if (seq_start[0] != 0) return LAWCAT_E_BAD_DESC;
+  const size_t eb = elem_bytes(desc);
+  // everything is checked for every sequence before anything is enqueued
+  for (int i = 0; i < desc->B; ++i) {
+    const long long len = (long long)seq_start[i + 1] - seq_start[i];
+    if (len < 1 || len > desc->T) return LAWCAT_E_BAD_DESC;
+    lawcat_desc one = *desc;
+    one.B = 1; one.T = (int32_t)len;
+    const size_t need = workspace_bytes_checked(&one, LAWCAT_CALL_LAYER_PREFILL);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return LAWCAT_E_WORKSPACE;
+  }
+  const size_t qrow = (size_t)desc->Hq * desc->dk * eb, krow = (size_t)desc->Hkv * desc->dk * eb;
+  const size_t Wm = (size_t)(desc->conv_width - 1);
+  const size_t sz = (size_t)desc->Hkv * desc->dk * desc->dk, zz = (size_t)desc->Hkv * desc->dk;
+  auto at = [](const void* p, size_t bytes) -> const void* { return p ? static_cast<const char*>(p) + bytes : nullptr; };
+  auto atw = [](void* p, size_t bytes) -> void* { return p ? static_cast<char*>(p) + bytes : nullptr; };
+  for (int i = 0; i < desc->B; ++i) {
+    lawcat_desc one = *desc;
+    one.B = 1; one.T = seq_start[i + 1] - seq_start[i];
+    const size_t t0 = (size_t)seq_start[i];
+    st = layer_prefill_impl(&one, at(Q, t0 * qrow), at(K, t0 * krow), at(V, t0 * krow), at(gate_logits, t0 * krow), wq, wk,
+                            S0 ? S0 + i * sz : nullptr, z0 ? z0 + i * zz : nullptr, at(q_halo, i * Wm * qrow),
+                            at(k_halo, i * Wm * krow), atw(O, t0 * qrow), den_out ? den_out + t0 * desc->Hq : nullptr,
+                            S_out ? S_out + i * sz : nullptr, z_out ? z_out + i * zz : nullptr,
+                            atw(q_tail_out, i * Wm * qrow), atw(k_tail_out, i * Wm * krow), workspace, workspace_bytes,
+                            stream, nullptr, nullptr, /*den_rows_packed=*/true);
+    if (st != LAWCAT_OK) return st;
+  }
+  return LAWCAT_OK;
 }
 
 int lawcat_layer_prefill_fm(const lawcat_desc* desc, const void* Q, const void* K, const void* V,

@@ -21,7 +21,7 @@ CALL_CONV1D, CALL_GLA_PREFILL, CALL_GLA_STEP, CALL_LAYER_PREFILL, CALL_LAYER_PRE
 
 EXPORTS = (
     "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gla_prefill", "lawcat_gla_step", "lawcat_gla_steps",
-    "lawcat_conv1d_feature", "lawcat_layer_prefill", "lawcat_layer_prefill_fm", "lawcat_layer_prefill_static",
+    "lawcat_conv1d_feature", "lawcat_layer_prefill", "lawcat_layer_prefill_varlen", "lawcat_layer_prefill_fm", "lawcat_layer_prefill_static",
     "lawcat_layer_prefill_timed", "lawcat_status_string", "lawcat_version",
 )
 
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.lawcat_status_string.argtypes = [ci]
         L.lawcat_status_string.restype = ctypes.c_char_p
         L.lawcat_version.restype = ci
+        L.lawcat_layer_prefill_varlen.argtypes = [dp, ctypes.POINTER(ctypes.c_int32)] + [vp] * 17 + [sz, vp]
+        L.lawcat_layer_prefill_varlen.restype = ci
         L.lawcat_conv1d_feature.argtypes = [dp, ci] + [vp] * 7
         L.lawcat_conv1d_feature.restype = ci
         L.lawcat_layer_prefill_fm.argtypes = [dp] + [vp] * 18 + [sz, vp]
@@ -147,6 +149,26 @@ def layer_prefill(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O,
                                       _p(S0), _p(z0), _p(q_halo), _p(k_halo), _p(O), _p(den_out), _p(S_out),
                                       _p(z_out), _p(q_tail_out), _p(k_tail_out), _p(workspace), nbytes,
                                       _stream(stream)))
+
+
+def varlen_workspace_bytes(desc, seq_start):
+    """The largest lawcat_workspace_bytes over the sequences of a lawcat_layer_prefill_varlen call."""
+    need = 0
+    for i in range(len(seq_start) - 1):
+        one = Desc.from_buffer_copy(bytes(desc))
+        one.B, one.T = 1, int(seq_start[i + 1]) - int(seq_start[i])
+        need = max(need, workspace_bytes(one, CALL_LAYER_PREFILL))
+    return need
+
+
+def layer_prefill_varlen(desc, seq_start, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,
+                         q_tail_out, k_tail_out, workspace, stream=None):
+    starts = (ctypes.c_int32 * len(seq_start))(*[int(v) for v in seq_start])
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lawcat_layer_prefill_varlen(ctypes.byref(desc), starts, _p(Q), _p(K), _p(V), _p(gate_logits), _p(wq),
+                                             _p(wk), _p(S0), _p(z0), _p(q_halo), _p(k_halo), _p(O), _p(den_out), _p(S_out),
+                                             _p(z_out), _p(q_tail_out), _p(k_tail_out), _p(workspace), nbytes,
+                                             _stream(stream)))
 
 
 def conv1d_feature(desc, n_heads, x, w, wf, halo, y, tail_out, stream=None):

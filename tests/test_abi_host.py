@@ -195,3 +195,26 @@ def test_feature_map_entry_points_check_their_arguments():
     assert layer(d, A, need - 1) == -4
     assert layer(d, None, 0) == -4
     assert layer(lawcat.make_desc(1, 0, 4, 2, 64), A, need) == -2
+
+
+def test_varlen_entry_point_checks_every_sequence_first():
+    """lawcat_layer_prefill_varlen: offsets start at 0 and increase strictly, no length above desc.T, workspace
+    enough for the longest sequence -- all before anything is enqueued."""
+    L = lawcat.lib()
+    d = lawcat.make_desc(3, 4096, 32, 8, 64)
+
+    def call(starts, desc=d, ws=A, nbytes=1 << 30, den=None, Q=A):
+        arr = (ctypes.c_int32 * len(starts))(*starts)
+        return L.lawcat_layer_prefill_varlen(ctypes.byref(desc), arr, Q, A, A, A, A, A, None, None, None, None, A, den,
+                                             A, A, None, None, ws, nbytes, None)
+
+    assert call([1, 100, 200, 300]) == -2          # must start at 0
+    assert call([0, 100, 100, 300]) == -2          # empty sequence
+    assert call([0, 100, 50, 300]) == -2           # decreasing
+    assert call([0, 100, 200, 4500]) == -2         # longer than desc.T
+    assert call([0, 100, 200, 300], Q=None) == -1
+    assert call([0, 4096, 8192, 8292], ws=None, nbytes=0) == -4
+    need = lawcat.varlen_workspace_bytes(d, [0, 4096, 8192, 8292])
+    assert need == lawcat.workspace_bytes(lawcat.make_desc(1, 4096, 32, 8, 64), lawcat.CALL_LAYER_PREFILL) > 0
+    assert call([0, 4096, 8192, 8292], nbytes=need - 1) == -4
+    assert call([0, 100, 200, 300], den=ctypes.c_void_p(0x1004)) == -5

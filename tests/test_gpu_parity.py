@@ -375,6 +375,47 @@ def test_layer_prefill_with_linear_feature_map(oracle, name, T, phi, extras):
     assert np.array_equal(got["q_tail"], ref["q_tail"]) and np.array_equal(got["k_tail"], ref["k_tail"])
 
 
+# ------------------------------------------------------------------ sequences of different lengths, packed
+@pytest.mark.parametrize("name,lengths", [("tiny", (5, 130, 1, 64)), ("llama1b_8k", (700, 64, 1500, 1, 333)),
+                                          ("mistral7b_16k", (257, 1024, 16))])
+def test_layer_prefill_varlen(oracle, name, lengths):
+    """lawcat_layer_prefill_varlen: every sequence of the packed batch equals the oracle run on that sequence alone
+    (its own start state, conv halo, final state and conv tails)."""
+    base = WORKLOADS[name]
+    n, total = len(lengths), sum(lengths)
+    starts = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    wl = Workload(f"{name}_varlen", 1, total, base.Hq, base.Hkv, base.d, base.W, base.dtype)
+    x = make_inputs(wl, seed=17)                              # one packed token axis
+    per = Workload("per_seq", n, 1, base.Hq, base.Hkv, base.d, base.W, base.dtype)
+    ext = make_inputs(per, seed=18, halo=True, state=True)    # per-sequence start states and halos
+    _say("varlen", wl, lengths)
+    dt = H.tdtype(wl)
+    desc = H.desc_for(Workload("v", n, max(lengths), base.Hq, base.Hkv, base.d, base.W, base.dtype), feature_map=1)
+    Q, K, V, G = (H.dev(x[k][0], dt) for k in ("Q", "K", "V", "G"))
+    wq, wk = H.dev(x["wq"], dt), H.dev(x["wk"], dt)
+    S0, z0 = H.dev(ext["S0"]), H.dev(ext["z0"])
+    qh, kh = H.dev(ext["q_halo"], dt), H.dev(ext["k_halo"], dt)
+    O = torch.empty_like(Q)
+    den = torch.empty(total, wl.Hq, dtype=torch.float32, device="cuda")
+    S = torch.empty(n, wl.Hkv, wl.d, wl.d, dtype=torch.float32, device="cuda")
+    z = torch.empty(n, wl.Hkv, wl.d, dtype=torch.float32, device="cuda")
+    qt = torch.empty(n, wl.W - 1, wl.Hq, wl.d, dtype=dt, device="cuda")
+    kt = torch.empty(n, wl.W - 1, wl.Hkv, wl.d, dtype=dt, device="cuda")
+    ws = torch.empty(max(lawcat.varlen_workspace_bytes(desc, starts), 16), dtype=torch.uint8, device="cuda")
+    lawcat.layer_prefill_varlen(desc, starts, Q, K, V, G, wq, wk, S0, z0, qh, kh, O, den, S, z, qt, kt, ws)
+    torch.cuda.synchronize()
+    o_h, den_h, S_h, z_h, qt_h, kt_h = (H.host(t) for t in (O, den, S, z, qt, kt))
+    for i in range(n):
+        a, b = int(starts[i]), int(starts[i + 1])
+        one = Workload(f"{name}_seq{i}", 1, b - a, base.Hq, base.Hkv, base.d, base.W, base.dtype)
+        ref = oracle.layer_prefill(x["Q"][:, a:b], x["K"][:, a:b], x["V"][:, a:b], x["G"][:, a:b], x["wq"], x["wk"], 1,
+                                   1.0, 0.0, ext["S0"][i:i + 1], ext["z0"][i:i + 1], ext["q_halo"][i:i + 1],
+                                   ext["k_halo"][i:i + 1])
+        got = {"o": o_h[None, a:b], "den": den_h[None, a:b], "S": S_h[i:i + 1], "z": z_h[i:i + 1]}
+        _check_prefill(got, ref, one, 1, f"varlen[{name}] sequence {i} (T={b - a})")
+        assert np.array_equal(qt_h[i:i + 1], ref["q_tail"]) and np.array_equal(kt_h[i:i + 1], ref["k_tail"])
+
+
 # ------------------------------------------------------------------ continuation (conv cache + state)
 @pytest.mark.parametrize("name,T,T1", [("tiny", 256, 100), ("llama1b_8k", 900, 515), ("mistral7b_16k", 300, 2)])
 def test_split_prefill_equals_whole(oracle, name, T, T1):
