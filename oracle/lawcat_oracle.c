@@ -97,6 +97,33 @@ void lawcat_oracle_feature_linear(int B, int T, int H, int d, int group, const d
 }
 
 /*
+ * Section 4.2, where the gate comes from: "linear layers" followed by the sigmoid; the rank ablation of the
+ * appendix says which: two consecutive low-rank linear layers (rank 32 in the distilled models).  The logits
+ *   g[b,t,n] = sum_r ( sum_c x[b,t,c] * w1[r,c] ) * w2[n,r]  (+ bias[n])
+ * x: [B,T,dm] the layer input; w1: [rank,dm], w2: [N,rank] (out-features x in-features), bias: NULL or [N];
+ * N = Hkv * dk, so g is the [B,T,Hkv,dk] gate-logit tensor of the recurrence below.
+ */
+void lawcat_oracle_gate_project(int B, int T, int dm, int rank, int N, const double* x, const double* w1,
+                                const double* w2, const double* bias, double* g) {
+#pragma omp parallel for schedule(static)
+  for (long long bt = 0; bt < (long long)B * T; ++bt) {
+    const double* xr = x + (size_t)bt * dm;
+    double* gr = g + (size_t)bt * N;
+    double h[1024];
+    for (int r = 0; r < rank; ++r) {
+      double acc = 0.0;
+      for (int c = 0; c < dm; ++c) acc += xr[c] * w1[(size_t)r * dm + c];
+      h[r] = acc;
+    }
+    for (int n = 0; n < N; ++n) {
+      double acc = bias ? bias[n] : 0.0;
+      for (int r = 0; r < rank; ++r) acc += h[r] * w2[(size_t)n * rank + r];
+      gr[n] = acc;
+    }
+  }
+}
+
+/*
  * Section 4.2 recurrence, token by token.
  *   q: [B,T,Hq,dk]  k,g: [B,T,Hkv,dk]  v: [B,T,Hkv,dv]   (q, k are already q-dot, k-dot)
  *   S0: NULL or [B,Hkv,dk,dv];  z0: NULL or [B,Hkv,dk]

@@ -43,6 +43,8 @@ def _load():
         _lib.lawcat_oracle_gla_prefill.restype = None
         _lib.lawcat_oracle_feature_linear.argtypes = [ctypes.c_int] * 5 + [dp, dp, ctypes.c_int, dp]
         _lib.lawcat_oracle_feature_linear.restype = None
+        _lib.lawcat_oracle_gate_project.argtypes = [ctypes.c_int] * 5 + [dp, dp, dp, dp, dp]
+        _lib.lawcat_oracle_gate_project.restype = None
         _lib.lawcat_oracle_max_threads.restype = ctypes.c_int
     return _lib
 
@@ -88,6 +90,21 @@ def feature_linear(x, wf, feature_map: int = 0):
     y = np.empty_like(x)
     lib.lawcat_oracle_feature_linear(B, T, H, d, H // Hw, _ptr(x), _ptr(wf), int(feature_map), _ptr(y))
     return y
+
+
+def gate_project(x, w1, w2, bias=None, Hkv: int = 1):
+    """Section 4.2 / appendix (rank of the gate function): gate logits from the layer input through two
+    consecutive low-rank linear layers.  x [B,T,dm], w1 [rank,dm], w2 [N,rank], bias None or [N]; returns
+    [B,T,Hkv,N/Hkv]."""
+    lib = _load()
+    x, w1, w2 = _f64(x), _f64(w1), _f64(w2)
+    B, T, dm = x.shape
+    rank, N = w1.shape[0], w2.shape[0]
+    assert w1.shape == (rank, dm) and w2.shape == (N, rank) and rank <= 1024 and N % Hkv == 0
+    b = None if bias is None else _f64(bias)
+    g = np.empty((B, T, N), dtype=np.float64)
+    lib.lawcat_oracle_gate_project(B, T, dm, rank, N, _ptr(x), _ptr(w1), _ptr(w2), _ptr(b), _ptr(g))
+    return g.reshape(B, T, Hkv, N // Hkv)
 
 
 def gla_prefill(q, k, v, g, gate_scale: float = 1.0, eps: float = 0.0, S0=None, z0=None):

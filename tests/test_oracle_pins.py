@@ -305,6 +305,40 @@ def test_shared_linear_feature_map(oracle):
     np.testing.assert_allclose(r3["o"], r4["o"], rtol=0, atol=1e-13)
 
 
+def test_gate_projection_two_low_rank_layers(oracle):
+    """Gate logits = (x W1^T) W2^T + b (two consecutive linear layers, out x in weight layout): equals library
+    matmuls; a rank-1 pair has the closed form (x . u)(v_n); unit vectors pick single entries; the logits feed
+    the recurrence as its gate tensor."""
+    rng = np.random.default_rng(31)
+    B, T, dm, r, Hkv, d = 2, 7, 11, 3, 2, 5
+    N = Hkv * d
+    x, w1, w2, b = _rand(rng, B, T, dm), _rand(rng, r, dm), _rand(rng, N, r), _rand(rng, N)
+    g = oracle.gate_project(x, w1, w2, b, Hkv)
+    assert g.shape == (B, T, Hkv, d)
+    np.testing.assert_allclose(g.reshape(B, T, N), (x @ w1.T) @ w2.T + b, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(oracle.gate_project(x, w1, w2, None, Hkv), g - b.reshape(Hkv, d), rtol=1e-13, atol=1e-13)
+    # rank 1: every logit is the same projection of x times its own scale
+    u, v = _rand(rng, 1, dm), _rand(rng, N, 1)
+    g1 = oracle.gate_project(x, u, v, None, Hkv).reshape(B, T, N)
+    np.testing.assert_allclose(g1, (x @ u[0])[..., None] * v[:, 0], rtol=1e-13, atol=1e-13)
+    # unit vectors: w1 picks channels 4 and 9, w2 routes them to outputs 2 and 7 with weights 2 and -3
+    e1 = np.zeros((2, dm)); e1[0, 4] = 1.0; e1[1, 9] = 1.0
+    e2 = np.zeros((N, 2)); e2[2, 0] = 2.0; e2[7, 1] = -3.0
+    gp = oracle.gate_project(x, e1, e2, None, Hkv).reshape(B, T, N)
+    expect = np.zeros((B, T, N)); expect[..., 2] = 2.0 * x[..., 4]; expect[..., 7] = -3.0 * x[..., 9]
+    np.testing.assert_array_equal(gp, expect)
+    # swapped operand layouts must show
+    assert np.abs(g.reshape(B, T, N) - ((x @ w1.T) @ w2.T + b)[..., ::-1]).max() > 0.1
+    # and the logits are what the recurrence takes as G
+    q, k, vv = _rand(rng, B, T, Hkv, d), _rand(rng, B, T, Hkv, d), _rand(rng, B, T, Hkv, d)
+    r1 = oracle.gla_prefill(np.abs(q), np.abs(k), vv, g)
+    alpha = 1.0 / (1.0 + np.exp(-g))
+    S = np.zeros((B, Hkv, d, d))
+    for t in range(T):
+        S = alpha[:, t, :, :, None] * S + np.abs(k)[:, t, :, :, None] * vv[:, t, :, None, :]
+    np.testing.assert_allclose(r1["S"], S, rtol=1e-12, atol=1e-12)
+
+
 def test_continuation_split_prefill_and_steps(oracle):
     """prefill(T) == prefill(T1) then prefill(T-T1) with carried (S, z, conv tails) == T single steps."""
     rng = np.random.default_rng(12)
