@@ -190,6 +190,23 @@ def run_side_ops(wl, steps=30):
     e1.record()
     torch.cuda.synchronize()
     fm_layer_ms = e0.elapsed_time(e1) / steps
+    # gate logits from the layer input (two rank-32 linear layers): reads d_model * 2 B, writes Hkv * d * 2 B per token
+    dm = 2048 if wl.d == 64 else 4096
+    gxs = [torch.randn(wl.B, wl.T, dm, device="cuda").to(dt) for _ in range(nset)]
+    gw1 = (torch.randn(32, dm, device="cuda") * dm ** -0.5).to(dt)
+    gw2 = (torch.randn(wl.Hkv * wl.d, 32, device="cuda") * 32 ** -0.5).to(dt)
+    gb = (0.5 * torch.randn(wl.Hkv * wl.d, device="cuda")).to(dt)
+    gout = torch.empty(wl.B, wl.T, wl.Hkv, wl.d, dtype=dt, device="cuda")
+    for i in range(3):
+        lawcat.gate_project(desc, dm, 32, gxs[i % nset], gw1, gw2, gb, gout)
+    e0.record()
+    for i in range(steps):
+        lawcat.gate_project(desc, dm, 32, gxs[i % nset], gw1, gw2, gb, gout)
+    e1.record()
+    torch.cuda.synchronize()
+    gate_ms = e0.elapsed_time(e1) / steps
+    gate_bytes = wl.B * wl.T * (dm + wl.Hkv * wl.d) * 2
+    del gxs
     # decode step
     d1 = lawcat.make_desc(wl.B, 1, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W, dtype=lawcat.DTYPE_BF16, feature_map=1)
     q = torch.rand(wl.B, wl.Hq, wl.d, device="cuda").to(dt) + 0.5
@@ -230,6 +247,8 @@ def run_side_ops(wl, steps=30):
             "conv1d_feature_q": {"ms": feat_ms, "GB/s": conv_bytes / (feat_ms * 1e-3) / 1e9,
                                  "frac_of_hbm_peak": conv_bytes / (feat_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                                  "mfma_TFLOP/s": 2 * xs[0].numel() * wl.d / (feat_ms * 1e-3) / 1e12},
+            "gate_project": {"ms": gate_ms, "d_model": dm, "rank": 32, "GB/s": gate_bytes / (gate_ms * 1e-3) / 1e9,
+                             "frac_of_hbm_peak": gate_bytes / (gate_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "layer_prefill_fm": {"ms": fm_layer_ms, "tokens_per_s": wl.B * wl.T / (fm_layer_ms * 1e-3)},
             "gla_step": {"us_per_step": step_us, "state_bytes_per_step": 2 * S.numel() * 4}}
 

@@ -110,6 +110,20 @@ LAWCAT_API int lawcat_conv1d_feature(const lawcat_desc* desc, int n_heads, const
                           const void* wf, const void* halo, void* y, void* tail_out, void* stream);
 
 /*
+ * Section 4.2, where the gate logits come from ("linear layers" before the sigmoid; the appendix's ablation on the
+ * rank of the gate function: two consecutive low-rank linear layers, rank 32 in the distilled models):
+ *   gate_logits[b,t,n] = sum_r ( sum_c x[b,t,c] * w1[r,c] ) * w2[n,r] + bias[n]
+ *   x [B,T,d_model] the layer input; w1 [rank,d_model]; w2 [Hkv*dk,rank] (out-features x in-features, as linear
+ *   layers are stored); bias [Hkv*dk], nullable; all in the storage type.  gate_logits [B,T,Hkv,dk]: the tensor
+ *   the prefill and step calls take.
+ * d_model and rank multiples of 8 with (d_model + rank) * 4 <= 65536, else LAWCAT_E_UNSUPPORTED.  bf16 storage
+ * with rank 32, d_model % 128 == 0 and Hkv*dk % 128 == 0 runs on the matrix cores (fp32 accumulation; the
+ * rank-32 intermediate is rounded to bf16 once, as an operand); every other case in plain fp32.
+ */
+LAWCAT_API int lawcat_gate_project(const lawcat_desc* desc, int d_model, int rank, const void* x, const void* w1,
+                        const void* w2, const void* bias, void* gate_logits, void* stream);
+
+/*
  * Section 4.2, prefill: for t = 1..T
  *   S_t = diag(alpha_t) S_{t-1} + k_t^T v_t,   z_t = alpha_t (.) z_{t-1} + k_t,
  *   o_t = q_t S_t / (q_t . z_t + eps)

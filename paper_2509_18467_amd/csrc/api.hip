@@ -149,6 +149,23 @@ int lawcat_conv1d_feature(const lawcat_desc* desc, int n_heads, const void* x, c
   return hip_status(launch_conv_tail(p, hs));
 }
 
+int lawcat_gate_project(const lawcat_desc* desc, int d_model, int rank, const void* x, const void* w1, const void* w2,
+                        const void* bias, void* gate_logits, void* stream) {
+  int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (d_model < 1 || rank < 1) return LAWCAT_E_BAD_DESC;
+  // rows of x and of the weights are read 16 bytes at a time; the one-token-per-workgroup kernel keeps a row of x
+  // and the intermediate in 64 KB of LDS
+  if (d_model % 8 != 0 || rank % 8 != 0 || ((size_t)d_model + rank) * sizeof(float) > 64 * 1024) return LAWCAT_E_UNSUPPORTED;
+  if (x == nullptr || w1 == nullptr || w2 == nullptr || gate_logits == nullptr) return LAWCAT_E_NULL;
+  if (!aligned16(x) || !aligned16(w1) || !aligned16(w2) || !aligned16(bias) || !aligned16(gate_logits)) return LAWCAT_E_ALIGN;
+  GateProjectParams p{};
+  p.x = x; p.w1 = w1; p.w2 = w2; p.bias = bias; p.g = gate_logits;
+  p.B = desc->B; p.T = desc->T; p.dm = d_model; p.rank = rank; p.N = desc->Hkv * desc->dk;
+  p.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
+  return hip_status(launch_gate_project(p, static_cast<hipStream_t>(stream)));
+}
+
 int lawcat_gla_prefill(const lawcat_desc* desc, const void* q, const void* k, const void* v,
                        const void* gate_logits, const float* S0, const float* z0, void* o, float* den_out,
                        float* S_out, float* z_out, void* workspace, size_t workspace_bytes, void* stream) {

@@ -25,6 +25,15 @@ hipError_t launch_conv1d(const ConvParams& p, hipStream_t stream);
 hipError_t launch_conv_tail(const ConvParams& p, hipStream_t stream);
 // Conv followed by the shared linear layer with nonlinearity (section 4.1): y = phi(conv(x) Wf), Wf [H / group, d, d]
 // in the storage type; head h uses matrix h / group.  p.tail_out is not written (see launch_conv_tail).
+// gate logits from the layer input: g = (x w1^T) w2^T + bias (two consecutive low-rank linear layers)
+struct GateProjectParams {
+  const void *x, *w1, *w2, *bias;  // [B,T,dm], [rank,dm], [N,rank], [N] or null; storage type
+  void* g;                         // [B,T,N]
+  int B, T, dm, rank, N;
+  int bf16;
+};
+hipError_t launch_gate_project(const GateProjectParams& p, hipStream_t stream);
+
 hipError_t launch_conv_feature(const ConvParams& p, const void* wf, int group, hipStream_t stream);
 
 struct RecurrentParams {

@@ -95,3 +95,21 @@ def make_feature_weights(wl: Workload, seed: int = 0) -> np.ndarray:
     wf *= np.float32(1.0 / np.sqrt(wl.d))
     wf += np.eye(wl.d, dtype=np.float32)
     return round_to_bf16(wf) if wl.dtype == "bf16" else wf
+
+
+def make_gate_inputs(wl: Workload, d_model: int, rank: int = 32, seed: int = 0, bias: bool = True) -> dict:
+    """Layer input and the two low-rank gate matrices: x ~ N(0,1) (a normalized hidden state), w1 [rank,d_model]
+    ~ N(0, 1/d_model), w2 [Hkv*d, rank] ~ N(0, 1/rank), bias ~ N(0, 1/4): gate logits of unit scale, as the G of
+    make_inputs.  A generator of its own."""
+    rng = np.random.default_rng([seed, 0x4750])
+    f32 = np.float32
+    N = wl.Hkv * wl.d
+    out = {"x": rng.standard_normal((wl.B, wl.T, d_model), dtype=f32),
+           "w1": rng.standard_normal((rank, d_model), dtype=f32) * f32(d_model ** -0.5),
+           "w2": rng.standard_normal((N, rank), dtype=f32) * f32(rank ** -0.5)}
+    if bias:
+        out["bias"] = rng.standard_normal((N,), dtype=f32) * f32(0.5)
+    if wl.dtype == "bf16":
+        for k in list(out):
+            out[k] = round_to_bf16(out[k])
+    return out

@@ -20,7 +20,7 @@ CARRY_AUTO, CARRY_SEQUENTIAL, CARRY_TWO_LEVEL = 0, 1, 2
 CALL_CONV1D, CALL_GLA_PREFILL, CALL_GLA_STEP, CALL_LAYER_PREFILL, CALL_LAYER_PREFILL_FM = 0, 1, 2, 3, 4
 
 EXPORTS = (
-    "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gla_prefill", "lawcat_gla_step", "lawcat_gla_steps",
+    "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gate_project", "lawcat_gla_prefill", "lawcat_gla_step", "lawcat_gla_steps",
     "lawcat_conv1d_feature", "lawcat_layer_prefill", "lawcat_layer_prefill_varlen", "lawcat_layer_prefill_fm", "lawcat_layer_prefill_static",
     "lawcat_layer_prefill_timed", "lawcat_status_string", "lawcat_version",
 )
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.lawcat_status_string.argtypes = [ci]
         L.lawcat_status_string.restype = ctypes.c_char_p
         L.lawcat_version.restype = ci
+        L.lawcat_gate_project.argtypes = [dp, ci, ci] + [vp] * 6
+        L.lawcat_gate_project.restype = ci
         L.lawcat_layer_prefill_varlen.argtypes = [dp, ctypes.POINTER(ctypes.c_int32)] + [vp] * 17 + [sz, vp]
         L.lawcat_layer_prefill_varlen.restype = ci
         L.lawcat_conv1d_feature.argtypes = [dp, ci] + [vp] * 7
@@ -149,6 +151,11 @@ def layer_prefill(desc, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O,
                                       _p(S0), _p(z0), _p(q_halo), _p(k_halo), _p(O), _p(den_out), _p(S_out),
                                       _p(z_out), _p(q_tail_out), _p(k_tail_out), _p(workspace), nbytes,
                                       _stream(stream)))
+
+
+def gate_project(desc, d_model, rank, x, w1, w2, bias, gate_logits, stream=None):
+    _check(lib().lawcat_gate_project(ctypes.byref(desc), d_model, rank, _p(x), _p(w1), _p(w2), _p(bias), _p(gate_logits),
+                                     _stream(stream)))
 
 
 def varlen_workspace_bytes(desc, seq_start):

@@ -127,6 +127,16 @@ def run_conv_feature(wl: Workload, x, w, wf, halo=None, feature_map=1):
     return host(y), (host(tail) if tail is not None else None)
 
 
+def run_gate_project(wl: Workload, gi: dict, d_model: int, rank: int):
+    dt = tdtype(wl)
+    d = desc_for(wl)
+    x, w1, w2, b = (dev(gi.get(k), dt) for k in ("x", "w1", "w2", "bias"))
+    g = torch.empty(wl.B, wl.T, wl.Hkv, wl.d, dtype=dt, device="cuda")
+    lawcat.gate_project(d, d_model, rank, x, w1, w2, b, g)
+    torch.cuda.synchronize()
+    return host(g)
+
+
 def run_gla_prefill(wl: Workload, q, k, v, g, S0=None, z0=None, **desc_kw):
     dt = tdtype(wl)
     d = desc_for(wl, **desc_kw)

@@ -218,3 +218,18 @@ def test_varlen_entry_point_checks_every_sequence_first():
     assert need == lawcat.workspace_bytes(lawcat.make_desc(1, 4096, 32, 8, 64), lawcat.CALL_LAYER_PREFILL) > 0
     assert call([0, 4096, 8192, 8292], nbytes=need - 1) == -4
     assert call([0, 100, 200, 300], den=ctypes.c_void_p(0x1004)) == -5
+
+
+def test_gate_project_argument_checks():
+    L = lawcat.lib()
+    d = lawcat.make_desc(1, 4096, 32, 8, 64)
+
+    def call(dm=2048, rank=32, x=A, bias=None, desc=d):
+        return L.lawcat_gate_project(ctypes.byref(desc), dm, rank, x, A, A, bias, A, None)
+
+    assert call(x=None) == -1
+    assert call(dm=0) == -2 and call(rank=0) == -2
+    assert call(dm=2047) == -3 and call(rank=12) == -3
+    assert call(dm=16384) == -3                     # a row of x plus the intermediate must fit 64 KB of LDS as fp32
+    assert call(bias=ctypes.c_void_p(0x1008)) == -5
+    assert call(desc=lawcat.make_desc(1, 0, 32, 8, 64)) == -2

@@ -9,7 +9,8 @@ import pytest
 import torch
 
 from paper_2509_18467_amd import lawcat
-from paper_2509_18467_amd.inputs import WORKLOADS, Workload, make_feature_weights, make_inputs, round_to_bf16
+from paper_2509_18467_amd.inputs import (WORKLOADS, Workload, make_feature_weights, make_gate_inputs, make_inputs,
+                                        round_to_bf16)
 
 import helpers as H
 
@@ -75,6 +76,43 @@ def test_conv1d_feature(oracle, dtype, T, Hh, Hkv, d, W, phi, halo):
     if W > 1:
         full = np.concatenate([np.zeros((wl.B, W - 1, Hh, d)) if hl is None else hl, x], axis=1)
         assert np.array_equal(tail, full[:, -(W - 1):]), "tail rows must be bit-exact copies"
+
+
+# ------------------------------------------------------------------ gate logits from the layer input (section 4.2)
+@pytest.mark.parametrize("dtype,B,T,Hkv,d,dm,rank,bias", [
+    ("bf16", 1, 300, 8, 64, 2048, 32, True), ("bf16", 2, 77, 8, 128, 4096, 32, False), ("bf16", 1, 1, 2, 64, 128, 32, True),
+    ("bf16", 1, 8192, 8, 64, 2048, 32, True), ("bf16", 1, 4096, 8, 128, 4096, 32, True),
+    ("bf16", 3, 50, 3, 64, 256, 16, True), ("bf16", 1, 40, 2, 64, 264, 8, False),
+    ("fp32", 2, 33, 2, 64, 256, 32, True), ("fp32", 1, 20, 2, 128, 512, 16, False),
+])
+def test_gate_project(oracle, dtype, B, T, Hkv, d, dm, rank, bias):
+    """g = (x w1^T) w2^T + b: rank 32 on the matrix cores (ragged token counts, both layer shapes), other ranks
+    and fp32 storage on the plain kernel.  The logits are signed with unit scale: the bar is 2e-2 of RMS plus
+    one bf16 half-ulp of the sum of the absolute values of the second layer's terms (a stored logit at 4 sigma
+    alone carries 1.5e-2 of RMS), as for the other signed stage outputs."""
+    wl = Workload("gate", B, T, 4 * Hkv, Hkv, d, 4, dtype)
+    gi = make_gate_inputs(wl, dm, rank, seed=T, bias=bias)
+    _say("gate_project", wl, dm, rank, bias)
+    got = H.run_gate_project(wl, gi, dm, rank)
+    ref = oracle.gate_project(gi["x"], gi["w1"], gi["w2"], gi.get("bias"), Hkv)
+    h = np.abs(gi["x"].astype(np.float64) @ gi["w1"].astype(np.float64).T)
+    terms = (h @ np.abs(gi["w2"].astype(np.float64)).T + (np.abs(gi["bias"]) if bias else 0.0)).reshape(ref.shape)
+    r = H.assert_close(got, ref, wl, "gate logits", 1 if dtype == "bf16" else 0, terms)
+    _say("  error / bar", f"{r:.3f}", "max err / rms", f"{H.rel_rms_err(got, ref):.3e}")
+
+
+def test_gate_project_feeds_the_layer(oracle):
+    """Projected logits straight into lawcat_layer_prefill: equals the oracle's projection followed by its layer."""
+    wl = WORKLOADS["llama1b_8k"].with_T(1500)
+    x = make_inputs(wl, seed=3)
+    gi = make_gate_inputs(wl, 2048, 32, seed=3)
+    g_gpu = H.run_gate_project(wl, gi, 2048, 32)
+    x["G"] = g_gpu.astype(np.float32)                      # exactly what the GPU stored (bf16 values)
+    got = H.run_layer_prefill(wl, x, feature_map=1)
+    g_ref = oracle.gate_project(gi["x"], gi["w1"], gi["w2"], gi["bias"], wl.Hkv)
+    ref = oracle.layer_prefill(x["Q"], x["K"], x["V"], round_to_bf16(g_ref.astype(np.float32)), x["wq"], x["wk"], 1)
+    # the two gate tensors differ where a logit sits on a bf16 rounding boundary; the layer's outputs must still agree
+    _check_prefill(got, ref, wl, 1, "gate projection -> layer")
 
 
 # ------------------------------------------------------------------ GLA prefill (section 4.2)
