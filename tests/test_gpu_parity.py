@@ -82,6 +82,7 @@ def test_conv1d_feature(oracle, dtype, T, Hh, Hkv, d, W, phi, halo):
 @pytest.mark.parametrize("dtype,B,T,Hkv,d,dm,rank,bias", [
     ("bf16", 1, 300, 8, 64, 2048, 32, True), ("bf16", 2, 77, 8, 128, 4096, 32, False), ("bf16", 1, 1, 2, 64, 128, 32, True),
     ("bf16", 1, 8192, 8, 64, 2048, 32, True), ("bf16", 1, 4096, 8, 128, 4096, 32, True),
+    ("bf16", 1, 16411, 8, 64, 2048, 32, True), ("bf16", 2, 8200, 8, 128, 4096, 32, False),   # 32 tokens per workgroup
     ("bf16", 3, 50, 3, 64, 256, 16, True), ("bf16", 1, 40, 2, 64, 264, 8, False),
     ("fp32", 2, 33, 2, 64, 256, 32, True), ("fp32", 1, 20, 2, 128, 512, 16, False),
 ])
