@@ -59,3 +59,72 @@ def test_layer_prefill_in_a_captured_graph(name, T):
         for got, ref, what in ((gO, eO, "o"), (gden, eden, "den"), (gS, eS, "S"), (gz, ez, "z")):
             assert torch.equal(got.view(torch.int16 if got.dtype == dt else torch.int32),
                                ref.view(torch.int16 if ref.dtype == dt else torch.int32)), f"replay {rep}: {what} differs"
+
+
+def test_projection_feature_map_layer_and_decode_block_in_one_graph():
+    """One captured graph holding a layer's whole chain -- gate logits from the layer input, the layer with its
+    linear feature map (workspace passed in), the same layer through the entry point that carries its scratch
+    inside the library, and a block of decode steps continuing from the prefill state -- replayed on changing
+    inputs; every replay equals the eager chain bit for bit."""
+    from paper_2509_18467_amd.inputs import make_feature_weights, make_gate_inputs
+
+    wl = WORKLOADS["llama1b_8k"].with_T(1300)
+    dt, dm, nb = torch.bfloat16, 2048, 24
+    desc = H.desc_for(wl, feature_map=1)
+    dn = lawcat.make_desc(wl.B, nb, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W, dtype=lawcat.DTYPE_BF16, feature_map=1)
+    xs = [make_inputs(wl, seed=50 + i) for i in range(3)]
+    gis = [make_gate_inputs(wl, dm, 32, seed=50 + i) for i in range(3)]
+    wf = H.dev(make_feature_weights(wl, seed=1), dt)
+    names = ("Q", "K", "V", "wq", "wk")
+    st = {n: H.dev(xs[0][n], dt) for n in names}
+    gx, gw1, gw2, gb = (H.dev(gis[0][k], dt) for k in ("x", "w1", "w2", "bias"))
+    # decode inputs: positive features (as phi would give), fixed
+    qn = (torch.rand(wl.B, nb, wl.Hq, wl.d, device="cuda") + 0.5).to(dt)
+    kn = (torch.rand(wl.B, nb, wl.Hkv, wl.d, device="cuda") + 0.5).to(dt)
+    vn = torch.randn(wl.B, nb, wl.Hkv, wl.d, device="cuda").to(dt)
+    gn = torch.randn(wl.B, nb, wl.Hkv, wl.d, device="cuda").to(dt)
+    ws = lawcat.alloc_workspace(desc, lawcat.CALL_LAYER_PREFILL_FM)
+
+    def buffers():
+        return {"G": torch.empty(wl.B, wl.T, wl.Hkv, wl.d, dtype=dt, device="cuda"),
+                "O": torch.empty_like(st["Q"]), "O2": torch.empty_like(st["Q"]),
+                "S": torch.empty(wl.B, wl.Hkv, wl.d, wl.d, device="cuda"), "z": torch.empty(wl.B, wl.Hkv, wl.d, device="cuda"),
+                "S2": torch.empty(wl.B, wl.Hkv, wl.d, wl.d, device="cuda"), "z2": torch.empty(wl.B, wl.Hkv, wl.d, device="cuda"),
+                "on": torch.empty_like(qn)}
+
+    def chain(b):
+        lawcat.gate_project(desc, dm, 32, gx, gw1, gw2, gb, b["G"])
+        lawcat.layer_prefill_fm(desc, st["Q"], st["K"], st["V"], b["G"], st["wq"], st["wk"], wf, None, None, None, None,
+                                b["O"], None, b["S"], b["z"], None, None, ws)
+        lawcat.layer_prefill_static(desc, st["Q"], st["K"], st["V"], b["G"], st["wq"], st["wk"], None, None, None, None,
+                                    b["O2"], None, b["S2"], b["z2"], None, None)
+        lawcat.gla_steps(dn, qn, kn, vn, gn, b["S"], b["z"], b["on"])      # continues from the prefill state, in place
+
+    gbuf = buffers()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        chain(gbuf)                                         # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain(gbuf)
+    for rep in range(4):
+        x, gi = xs[rep % 3], gis[rep % 3]
+        for n in names:
+            st[n].copy_(H.dev(x[n], dt))
+        gx.copy_(H.dev(gi["x"], dt)); gw1.copy_(H.dev(gi["w1"], dt)); gw2.copy_(H.dev(gi["w2"], dt)); gb.copy_(H.dev(gi["bias"], dt))
+        for t in gbuf.values():
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ebuf = buffers()
+        chain(ebuf)
+        torch.cuda.synchronize()
+        for k in gbuf:
+            a, b = gbuf[k], ebuf[k]
+            view = torch.int16 if a.dtype == dt else torch.int32
+            assert torch.equal(a.view(view), b.view(view)), f"replay {rep}: {k} differs"
+        assert torch.isfinite(gbuf["on"].float()).all() and torch.isfinite(gbuf["S"]).all()
