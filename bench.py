@@ -225,6 +225,28 @@ def run_side_ops(wl, steps=30):
     e1.record()
     torch.cuda.synchronize()
     step_us = e0.elapsed_time(e1) / n * 1e3
+    # the decode step over a batch of 256 sequences: bound by the state's traffic, not by the launch
+    Bb = 256
+    db = lawcat.make_desc(Bb, 1, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W, dtype=lawcat.DTYPE_BF16, feature_map=1)
+    qb = (torch.rand(Bb, wl.Hq, wl.d, device="cuda") + 0.5).to(dt)
+    kb = (torch.rand(Bb, wl.Hkv, wl.d, device="cuda") + 0.5).to(dt)
+    vb = torch.randn(Bb, wl.Hkv, wl.d, device="cuda").to(dt)
+    gb2 = torch.randn(Bb, wl.Hkv, wl.d, device="cuda").to(dt)
+    # two state sets in turn: 2 x 2 x (67 MB at d = 64, 268 MB at d = 128) do not fit the 256 MB Infinity Cache
+    Sb = [torch.zeros(Bb, wl.Hkv, wl.d, wl.d, device="cuda") for _ in range(2)]
+    zb = [torch.ones(Bb, wl.Hkv, wl.d, device="cuda") for _ in range(2)]
+    ob = torch.empty(Bb, wl.Hq, wl.d, dtype=dt, device="cuda")
+    for i in range(4):
+        lawcat.gla_step(db, qb, kb, vb, gb2, Sb[i % 2], zb[i % 2], ob)
+    nbs = 50
+    e0.record()
+    for i in range(nbs):
+        lawcat.gla_step(db, qb, kb, vb, gb2, Sb[i % 2], zb[i % 2], ob)
+    e1.record()
+    torch.cuda.synchronize()
+    batch_us = e0.elapsed_time(e1) / nbs * 1e3
+    batch_bytes = 2 * Sb[0].numel() * 4
+    del Sb, zb
     # the same decode in blocks of 256 tokens per launch (state on chip between the steps)
     nb = 256
     dn = lawcat.make_desc(wl.B, nb, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W, dtype=lawcat.DTYPE_BF16, feature_map=1)
@@ -242,6 +264,9 @@ def run_side_ops(wl, steps=30):
     torch.cuda.synchronize()
     block_us = e0.elapsed_time(e1) / (10 * nb) * 1e3
     return {"gla_steps_block256": {"us_per_step": block_us},
+            "gla_step_batch256": {"us_per_step": batch_us, "state_bytes_per_step": batch_bytes,
+                                  "GB/s": batch_bytes / (batch_us * 1e-6) / 1e9,
+                                  "frac_of_hbm_peak": batch_bytes / (batch_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
             "conv1d_causal_q": {"ms": conv_ms, "GB/s": conv_bytes / (conv_ms * 1e-3) / 1e9,
                                 "frac_of_hbm_peak": conv_bytes / (conv_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "conv1d_feature_q": {"ms": feat_ms, "GB/s": conv_bytes / (feat_ms * 1e-3) / 1e9,
