@@ -26,12 +26,17 @@
  *    O.  S, z and den are always fp32.  Arithmetic accumulates in fp32.
  *  - The gate is per key channel: alpha[t,c] = sigmoid(gate_logits[t,c])^gate_scale
  *    (section 4.2: linear layers followed by a sigmoid; G_t = alpha_t^T 1).
+ *    One approximation, bf16 prefill only: the matrix-core kernels floor alpha at 2^-13 per step (gate logits
+ *    below -9.0 at gate_scale 1), so that the reciprocal decay products inside an 8-token half chunk stay below
+ *    2^104.  What is lost is a factor that is already below 1.3e-4 of what it multiplies, i.e. under the bf16
+ *    resolution of the operands; logits of -30 everywhere, +30 everywhere and gate_scale 0 .. 16 meet the same
+ *    tolerance as ordinary gates.  fp32 storage, lawcat_gla_step and lawcat_gla_steps do not clamp.
  *  - Return value: LAWCAT_OK or a negative lawcat_status.  All argument checks run on
  *    the host before anything is enqueued; after an error the outputs are unspecified.
  *    A zero denominator is not an error: IEEE inf/nan is returned as the last equation
  *    of section 4.2 gives it.
- *  - Inputs and outputs must not overlap, except S/z in lawcat_gla_step (updated in
- *    place).  All pointers must be 16-byte aligned.
+ *  - Inputs and outputs must not overlap, except S/z in lawcat_gla_step and lawcat_gla_steps (updated
+ *    in place).  All pointers must be 16-byte aligned.
  */
 #ifndef LAWCAT_H_
 #define LAWCAT_H_
