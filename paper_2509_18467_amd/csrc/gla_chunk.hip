@@ -20,12 +20,14 @@ ChunkPlan make_chunk_plan(int B, int T, int Hkv, int d, int carry_mode, int segm
     seg_len = segment;
   } else {
     // enough workgroups to fill 256 compute units once (two 4-wave teams per unit at head dim 64, one
-    // 8-wave team at 128), segments no shorter than 128 tokens
+    // 8-wave team at 128).  Segments of two granules (128 tokens) at least, except where even those would leave
+    // more than half of the chip without a workgroup: short sequences are bound by the serial work of one
+    // workgroup, and one-granule segments halve it (T = 1K .. 2K: 31 -> 23 us at head dim 64, 51 -> 41 at 128)
     const int slots = d == 64 ? 512 : 256;
     const int want = (slots + heads - 1) / heads;
     seg_len = (T + want - 1) / want;
     seg_len = (seg_len + 63) / 64 * 64;
-    if (seg_len < 128) seg_len = 128;
+    if (seg_len < 128) seg_len = (long long)((T + 127) / 128) * heads * 2 <= slots ? 64 : 128;
   }
   p.seg_len = seg_len;
   p.nseg = (T + seg_len - 1) / seg_len;
