@@ -190,6 +190,34 @@ def run_side_ops(wl, steps=30):
     e1.record()
     torch.cuda.synchronize()
     fm_layer_ms = e0.elapsed_time(e1) / steps
+    # the same number of tokens as 24 packed sequences of 256 .. 4096 tokens: one set of launches for the batch
+    # (offsets on the device) against one call per sequence
+    lengths = [4096, 2048, 1024, 512, 256, 256] * (wl.B * wl.T // 8192) if wl.B * wl.T % 8192 == 0 else [wl.B * wl.T]
+    starts = [0]
+    for n_ in lengths:
+        starts.append(starts[-1] + n_)
+    dv = lawcat.make_desc(len(lengths), max(lengths), wl.Hq, wl.Hkv, wl.d, conv_width=wl.W, dtype=lawcat.DTYPE_BF16,
+                          feature_map=1)
+    need = max(lawcat.varlen_workspace_bytes(dv, starts, True), lawcat.varlen_workspace_bytes(dv, starts, False), 16)
+    wsv = torch.empty(need, dtype=torch.uint8, device="cuda")
+    starts_dev = torch.tensor(starts, dtype=torch.int32, device="cuda")
+    Sv = torch.empty(len(lengths), wl.Hkv, wl.d, wl.d, device="cuda")
+    zv = torch.empty(len(lengths), wl.Hkv, wl.d, device="cuda")
+    varlen_ms = {}
+    for tag, dev_arr in (("one_launch", starts_dev), ("per_sequence_calls", None)):
+        def vstep(i):
+            j = i % nset
+            lawcat.layer_prefill_varlen(dv, starts, xs[j].view(-1, wl.Hq, wl.d), Ks[j].view(-1, wl.Hkv, wl.d),
+                                        Vs[j].view(-1, wl.Hkv, wl.d), Gs[j].view(-1, wl.Hkv, wl.d), w, wk, None, None, None,
+                                        None, ys[j].view(-1, wl.Hq, wl.d), None, Sv, zv, None, None, wsv, seq_start_dev=dev_arr)
+        for i in range(3):
+            vstep(i)
+        e0.record()
+        for i in range(steps):
+            vstep(i)
+        e1.record()
+        torch.cuda.synchronize()
+        varlen_ms[tag] = e0.elapsed_time(e1) / steps
     # gate logits from the layer input (two rank-32 linear layers): reads d_model * 2 B, writes Hkv * d * 2 B per token
     dm = 2048 if wl.d == 64 else 4096
     gxs = [torch.randn(wl.B, wl.T, dm, device="cuda").to(dt) for _ in range(nset)]
@@ -274,6 +302,9 @@ def run_side_ops(wl, steps=30):
                                  "mfma_TFLOP/s": 2 * xs[0].numel() * wl.d / (feat_ms * 1e-3) / 1e12},
             "gate_project": {"ms": gate_ms, "d_model": dm, "rank": 32, "GB/s": gate_bytes / (gate_ms * 1e-3) / 1e9,
                              "frac_of_hbm_peak": gate_bytes / (gate_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "layer_prefill_varlen": {"sequences": len(lengths), "tokens": starts[-1], "ms_one_launch": varlen_ms["one_launch"],
+                                     "ms_per_sequence_calls": varlen_ms["per_sequence_calls"],
+                                     "tokens_per_s_one_launch": starts[-1] / (varlen_ms["one_launch"] * 1e-3)},
             "layer_prefill_fm": {"ms": fm_layer_ms, "tokens_per_s": wl.B * wl.T / (fm_layer_ms * 1e-3)},
             "gla_step": {"us_per_step": step_us, "state_bytes_per_step": 2 * S.numel() * 4}}
 

@@ -179,18 +179,24 @@ LAWCAT_API int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, cons
  * lawcat_layer_prefill for sequences of different lengths packed back to back (continuous batching, chunked
  * prefill of several requests): section 4.2's recurrence restarts at every sequence boundary, and section 4.1's
  * conv does not reach across it.  desc->B = number of sequences, desc->T = an upper bound of their lengths.
- *   seq_start  HOST array of B + 1 token offsets, seq_start[0] = 0, strictly increasing: sequence i owns
- *              tokens seq_start[i] .. seq_start[i+1] - 1; total = seq_start[B]
+ *   seq_start      HOST array of B + 1 token offsets, seq_start[0] = 0, strictly increasing: sequence i owns
+ *                  tokens seq_start[i] .. seq_start[i+1] - 1; total = seq_start[B]
+ *   seq_start_dev  nullable DEVICE copy of the same B + 1 offsets (4-byte aligned)
  *   Q, O [total,Hq,dk]   K, V, gate_logits [total,Hkv,dk]   den_out [total,Hq] (nullable)
  *   S0, z0, S_out, z_out, q_halo, k_halo, q_tail_out, k_tail_out: per sequence, shaped as in
  *   lawcat_layer_prefill with B sequences (chunked prefill: feed a sequence's S_out, z_out and tails back in).
- * One lawcat_layer_prefill with B = 1 per sequence, enqueued in order on `stream`; they share `workspace`,
- * which must cover lawcat_workspace_bytes(desc_i, LAWCAT_CALL_LAYER_PREFILL) for desc_i = desc with B = 1 and
- * T = each length.  All sequences are checked before anything is enqueued: a length below 1 or above desc->T
- * is LAWCAT_E_BAD_DESC.
+ * With seq_start_dev and bf16 storage the whole batch is ONE set of launches: the kernels read each sequence's
+ * first row and length from the device array, and the segments are cut as for one sequence of all the tokens, so
+ * that the workgroups are about as many as the chip holds whatever the mix of lengths.  Otherwise (no device
+ * copy, or fp32 storage): one lawcat_layer_prefill with B = 1 per sequence, enqueued in order on `stream`,
+ * sharing `workspace`.  Workspace size for either form: lawcat_varlen_workspace_bytes (one_launch = whether
+ * seq_start_dev will be passed).  All sequences are checked on the host before anything is enqueued: a length
+ * below 1 or above desc->T is LAWCAT_E_BAD_DESC.
  */
-LAWCAT_API int lawcat_layer_prefill_varlen(const lawcat_desc* desc, const int32_t* seq_start, const void* Q,
-                                const void* K, const void* V, const void* gate_logits, const void* wq,
+LAWCAT_API size_t lawcat_varlen_workspace_bytes(const lawcat_desc* desc, const int32_t* seq_start, int one_launch);
+
+LAWCAT_API int lawcat_layer_prefill_varlen(const lawcat_desc* desc, const int32_t* seq_start,
+                                const int32_t* seq_start_dev, const void* Q, const void* K, const void* V, const void* gate_logits, const void* wq,
                                 const void* wk, const float* S0, const float* z0, const void* q_halo,
                                 const void* k_halo, void* O, float* den_out, float* S_out, float* z_out,
                                 void* q_tail_out, void* k_tail_out, void* workspace, size_t workspace_bytes,

@@ -3,6 +3,7 @@
 // error paths can be exercised on a machine without a GPU.
 #include "../../include/lawcat.h"
 
+#include <algorithm>
 #include <cmath>
 #include <mutex>
 
@@ -101,6 +102,34 @@ size_t workspace_bytes_checked(const lawcat_desc* d, int which) {
     default:
       return 0;
   }
+}
+
+// Segments of a packed batch of sequences (one set of launches): cut as for ONE sequence of all the tokens, so that
+// the workgroups are about as many as the chip holds and about equally long whatever the mix of lengths; slots are
+// laid out for the longest sequence.
+ChunkPlan varlen_plan(const lawcat_desc* d, const int32_t* seq_start) {
+  const long long total = seq_start[d->B];
+  int longest = 1;
+  for (int i = 0; i < d->B; ++i) longest = std::max(longest, (int)(seq_start[i + 1] - seq_start[i]));
+  ChunkPlan one = make_chunk_plan(1, (int)std::min<long long>(total, 0x7fffffc0LL), d->Hkv, d->dk, d->carry_mode, d->segment);
+  ChunkPlan p;
+  const int whole = (longest + 63) / 64 * 64;
+  p.seg_len = std::min(one.seg_len, whole);
+  if (d->carry_mode == LAWCAT_CARRY_SEQUENTIAL) p.seg_len = whole;
+  if (d->segment == 0 && d->carry_mode != LAWCAT_CARRY_SEQUENTIAL) {
+    // every sequence rounds its segment count up: lengthen the segments until the workgroups fit the chip in one
+    // round (a few too many would double the time of the pass)
+    const long long slots = d->dk == 64 ? 512 : 256;
+    auto groups = [&](int seg_len) {
+      long long n = 0;
+      for (int i = 0; i < d->B; ++i) n += (seq_start[i + 1] - seq_start[i] + seg_len - 1) / seg_len;
+      return n * d->Hkv;
+    };
+    while (p.seg_len < whole && groups(p.seg_len) > slots) p.seg_len += 64;
+  }
+  p.nseg = (longest + p.seg_len - 1) / p.seg_len;
+  p.workspace_bytes = p.nseg > 1 ? (size_t)d->B * d->Hkv * p.nseg * ((d->dk * d->dk + 2 * d->dk) * sizeof(float) + sizeof(int)) : 0;
+  return p;
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? LAWCAT_OK : LAWCAT_E_HIP; }
@@ -300,7 +329,24 @@ int lawcat_layer_prefill(const lawcat_desc* desc, const void* Q, const void* K, 
                             q_tail_out, k_tail_out, workspace, workspace_bytes, stream, nullptr, nullptr);
 }
 
-int lawcat_layer_prefill_varlen(const lawcat_desc* desc, const int32_t* seq_start, const void* Q, const void* K,
+size_t lawcat_varlen_workspace_bytes(const lawcat_desc* desc, const int32_t* seq_start, int one_launch) {
+  if (check_desc(desc, true) != LAWCAT_OK || seq_start == nullptr || seq_start[0] != 0) return 0;
+  for (int i = 0; i < desc->B; ++i) {
+    const long long len = (long long)seq_start[i + 1] - seq_start[i];
+    if (len < 1 || len > desc->T) return 0;
+  }
+  if (one_launch && prefill_path(desc) == Path::kChunkBf16) return varlen_plan(desc, seq_start).workspace_bytes;
+  size_t need = 0;
+  for (int i = 0; i < desc->B; ++i) {
+    lawcat_desc one = *desc;
+    one.B = 1; one.T = seq_start[i + 1] - seq_start[i];
+    need = std::max(need, workspace_bytes_checked(&one, LAWCAT_CALL_LAYER_PREFILL));
+  }
+  return need;
+}
+
+int lawcat_layer_prefill_varlen(const lawcat_desc* desc, const int32_t* seq_start, const int32_t* seq_start_dev,
+                                const void* Q, const void* K,
                                 const void* V, const void* gate_logits, const void* wq, const void* wk,
                                 const float* S0, const float* z0, const void* q_halo, const void* k_halo, void* O,
                                 float* den_out, float* S_out, float* z_out, void* q_tail_out, void* k_tail_out,
@@ -313,12 +359,30 @@ int lawcat_layer_prefill_varlen(const lawcat_desc* desc, const int32_t* seq_star
       !aligned16(O) || !aligned16(den_out) || !aligned16(S_out) || !aligned16(z_out) ||
       !aligned16(q_tail_out) || !aligned16(k_tail_out) || !aligned16(workspace))
     return LAWCAT_E_ALIGN;
-  if (seq_start[0] != 0) return LAWCAT_E_BAD_DESC;
+  if (seq_start[0] != 0 || (reinterpret_cast<uintptr_t>(seq_start_dev) & 3u) != 0) return seq_start[0] != 0 ? LAWCAT_E_BAD_DESC : LAWCAT_E_ALIGN;
   const size_t eb = elem_bytes(desc);
   // everything is checked for every sequence before anything is enqueued
   for (int i = 0; i < desc->B; ++i) {
     const long long len = (long long)seq_start[i + 1] - seq_start[i];
     if (len < 1 || len > desc->T) return LAWCAT_E_BAD_DESC;
+  }
+  if (seq_start_dev != nullptr && prefill_path(desc) == Path::kChunkBf16) {
+    // one set of launches for the whole batch: the kernels take every sequence's first row and length from
+    // the device copy of the offsets; segments are cut for the longest sequence
+    const ChunkPlan plan = varlen_plan(desc, seq_start);
+    if (plan.workspace_bytes > 0 && (workspace == nullptr || workspace_bytes < plan.workspace_bytes)) return LAWCAT_E_WORKSPACE;
+    ChunkParams c{};
+    c.q = Q; c.k = K; c.v = V; c.g = gate_logits; c.wq = wq; c.wk = wk; c.q_halo = q_halo; c.k_halo = k_halo;
+    c.S0 = S0; c.z0 = z0; c.o = O; c.den_out = den_out; c.S_out = S_out; c.z_out = z_out;
+    c.workspace = workspace; c.seq_start = seq_start_dev;
+    c.B = desc->B; c.T = desc->T; c.Hq = desc->Hq; c.Hkv = desc->Hkv; c.d = desc->dk;
+    c.W = desc->conv_width; c.phi = desc->feature_map; c.fuse_conv = 1;
+    c.gate_scale = desc->gate_scale; c.eps = desc->eps; c.plan = plan;
+    c.q_tail = q_tail_out; c.k_tail = k_tail_out;
+    return hip_status(launch_gla_chunk(c, static_cast<hipStream_t>(stream)));
+  }
+  for (int i = 0; i < desc->B; ++i) {
+    const long long len = (long long)seq_start[i + 1] - seq_start[i];
     lawcat_desc one = *desc;
     one.B = 1; one.T = (int32_t)len;
     const size_t need = workspace_bytes_checked(&one, LAWCAT_CALL_LAYER_PREFILL);

@@ -44,6 +44,7 @@ hipError_t launch_gla_chunk(const ChunkParams& p, hipStream_t stream) {
   a.S0 = p.S0; a.z0 = p.z0; a.o = (bf16_t*)p.o; a.den_out = p.den_out; a.S_out = p.S_out; a.z_out = p.z_out;
   a.q_tail = (bf16_t*)p.q_tail; a.k_tail = (bf16_t*)p.k_tail;
   a.ws = (float*)p.workspace;
+  a.seq_start = p.seq_start;
   a.seg_live = reinterpret_cast<int*>(a.ws + (size_t)p.B * p.Hkv * p.plan.nseg * (p.d * p.d + 2 * p.d));
   a.B = p.B; a.T = p.T; a.Hq = p.Hq; a.Hkv = p.Hkv; a.W = p.W;
   a.seg_len = p.plan.seg_len; a.nseg = p.plan.nseg;

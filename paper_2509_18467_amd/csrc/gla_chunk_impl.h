@@ -29,6 +29,7 @@
 #pragma once
 #include <hip/hip_ext.h>
 
+#include <algorithm>
 #include <mutex>
 
 #include "kernels.h"
@@ -69,6 +70,10 @@ struct ChunkArgs {
   bf16_t *q_tail, *k_tail;
   float* ws;
   int* seg_live;   // [B*Hkv][nseg]: written by the state pass, 0 = the segment's total decay is exactly zero in every channel
+  // Sequences of different lengths packed along the token axis: device array of B + 1 row offsets, or null for B
+  // sequences of T tokens each.  With it, T is the longest length and nseg the segment count of that length;
+  // a shorter sequence uses the first ceil(length / seg_len) of its nseg workspace slots.
+  const int* seq_start;
   int B, T, Hq, Hkv, W;
   int group;   // query heads per kv head (Hq / Hkv)
   int qh0;     // first query head, within its group, that this launch of the output pass covers
@@ -443,11 +448,18 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
   const int g4 = l >> 4;    // MFMA lane group
   const int n = l & 15;     // MFMA row/column within a tile
   const int seg = blockIdx.x;
-  const int nseg_pass = OUTPUT ? a.nseg : a.nseg - 1;  // the first pass skips the last segment
-  const bool active = seg < nseg_pass;
   const int bh = blockIdx.y;
   const int b = bh / a.Hkv, hk = bh % a.Hkv;
-  const int T = a.T;
+  // this sequence: first row in the packed tensors, length, segments (token indices below are relative to row0)
+  size_t row0 = (size_t)b * a.T;
+  int T = a.T, nseg = a.nseg;
+  if (a.seq_start != nullptr) {
+    row0 = (size_t)a.seq_start[b];
+    T = a.seq_start[b + 1] - a.seq_start[b];
+    nseg = (T + a.seg_len - 1) / a.seg_len;
+  }
+  const int nseg_pass = OUTPUT ? nseg : nseg - 1;  // the first pass skips the last segment
+  const bool active = seg < nseg_pass;
   const int s0 = seg * a.seg_len;
   const int s1 = active ? min(T, s0 + a.seg_len) : s0;
 
@@ -462,8 +474,8 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
   // contribution as the state pass wrote it, the first from S0, z0.  The loads are issued here and reduced after
   // the conv weights below, so that the two latencies overlap.
   int live_any = 0;
-  if (OUTPUT && a.nseg > 1)
-    for (int j = tid; j < a.nseg - 1; j += G::TEAM) live_any |= a.seg_live[(size_t)bh * a.nseg + j];
+  if (OUTPUT && nseg > 1)
+    for (int j = tid; j < nseg - 1; j += G::TEAM) live_any |= a.seg_live[(size_t)bh * a.nseg + j];
 
   float* wl = reinterpret_cast<float*>(smem + G::kWl);
   if (CONV) {
@@ -484,12 +496,12 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
   // uniform row sources
   const unsigned kvstride = (unsigned)a.Hkv * D * 2, qstride = (unsigned)a.Hq * D * 2;
   const RowSrc srcK = make_row_src(
-      (const char*)a.k + ((size_t)b * T * a.Hkv + hk) * D * 2,
+      (const char*)a.k + (row0 * a.Hkv + hk) * D * 2,
       (CONV && a.k_halo) ? (const char*)a.k_halo + ((size_t)b * (a.W - 1) * a.Hkv + hk) * D * 2 : nullptr, kvstride, T, D * 2);
-  const RowSrc srcG = make_row_src((const char*)a.g + ((size_t)b * T * a.Hkv + hk) * D * 2, nullptr, kvstride, T, D * 2);
-  const RowSrc srcV = make_row_src((const char*)a.v + ((size_t)b * T * a.Hkv + hk) * D * 2, nullptr, kvstride, T, D * 2);
+  const RowSrc srcG = make_row_src((const char*)a.g + (row0 * a.Hkv + hk) * D * 2, nullptr, kvstride, T, D * 2);
+  const RowSrc srcV = make_row_src((const char*)a.v + (row0 * a.Hkv + hk) * D * 2, nullptr, kvstride, T, D * 2);
   const RowSrc srcQ = make_row_src(
-      (const char*)a.q + ((size_t)b * T * a.Hq + hk * a.group + a.qh0) * D * 2,
+      (const char*)a.q + (row0 * a.Hq + hk * a.group + a.qh0) * D * 2,
       (CONV && a.q_halo) ? (const char*)a.q_halo + ((size_t)b * (a.W - 1) * a.Hq + hk * a.group + a.qh0) * D * 2 : nullptr, qstride, T,
       (GR > 0 ? GR : 1) * D * 2);
   const unsigned coff = (unsigned)c0 * 2;
@@ -506,7 +518,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
     const float* zin = nullptr;
     if (OUTPUT && active) {
       bool scanned = false;
-      if (a.nseg > 1) {
+      if (nseg > 1) {
         // team-wide OR through the per-wave flag words (free until the granule loop; the barrier that ends the
         // prologue separates these reads from the loop's first writes)
         const bool wave_any = __builtin_amdgcn_ballot_w64(live_any != 0) != 0;
@@ -517,7 +529,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
         for (int j = 0; j < G::NW; ++j) any |= *reinterpret_cast<const int*>(smem + G::kFl + j * 4);
         scanned = __builtin_amdgcn_readfirstlane(any) != 0;
       }
-      if (scanned || (a.nseg > 1 && seg > 0)) {
+      if (scanned || (nseg > 1 && seg > 0)) {
         Sin = a.ws + ((size_t)bh * a.nseg + (scanned ? seg : seg - 1)) * G::kSlot;
         zin = Sin + D * D;
       } else {
@@ -729,7 +741,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
               const int tok = tq + n;
               const float rden = fast_rcp(o.den);
               if (tok < s1) {
-                bf16_t* orow = a.o + (((size_t)b * T + tok) * a.Hq + hk * a.group + a.qh0 + hh) * D;
+                bf16_t* orow = a.o + ((row0 + tok) * a.Hq + hk * a.group + a.qh0 + hh) * D;
 #pragma unroll
                 for (int ct = 0; ct < G::CT; ++ct) {
                   const uint2 pk = make_uint2(pack2(oacc[ct][0] * rden, oacc[ct][1] * rden),
@@ -737,7 +749,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
                   *reinterpret_cast<uint2*>(orow + 16 * (w * G::CT + ct) + 4 * g4) = pk;
                 }
                 if (a.den_out != nullptr && w == 0 && g4 == 0)
-                  a.den_out[((size_t)b * T + tok) * a.Hq + hk * a.group + a.qh0 + hh] = o.den;
+                  a.den_out[(row0 + tok) * a.Hq + hk * a.group + a.qh0 + hh] = o.den;
               }
             };
             HeadOps opA, opB;
@@ -801,7 +813,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
     Sdst = a.ws + ((size_t)bh * a.nseg + seg) * G::kSlot;
     zdst = Sdst + D * D;
     ddst = zdst + D;
-  } else if (seg == a.nseg - 1) {
+  } else if (seg == nseg - 1) {
     Sdst = a.S_out + (size_t)bh * D * D;
     zdst = a.z_out + (size_t)bh * D;
   }
@@ -820,7 +832,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
     if (!OUTPUT && tid == 0) a.seg_live[(size_t)bh * a.nseg + seg] = dead ? 0 : 1;
   }
   // ---- conv cache out: the last W-1 raw rows of [halo ; x] for this workgroup's heads
-  if (OUTPUT && CONV && seg == a.nseg - 1 && a.W > 1) {
+  if (OUTPUT && CONV && seg == nseg - 1 && a.W > 1) {
     const int Wm = a.W - 1;
     for (int e = tid; e < (GR + 1) * Wm * D; e += G::TEAM) {
       const int c = e % D, r = (e / D) % Wm, hh = e / (D * Wm);
@@ -832,7 +844,7 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
       const bf16_t* halo = isq ? a.q_halo : a.k_halo;
       const int src = T - Wm + r;
       bf16_t val = 0;
-      if (src >= 0) val = x[(((size_t)b * T + src) * H + head) * D + c];
+      if (src >= 0) val = x[((row0 + src) * H + head) * D + c];
       else if (halo != nullptr) val = halo[(((size_t)b * Wm + (Wm + src)) * H + head) * D + c];
       dst[(((size_t)b * Wm + r) * H + head) * D + c] = val;
     }
@@ -848,28 +860,40 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
 template <int D>
 __global__ void __launch_bounds__(256) segment_scan_kernel(float* __restrict__ ws, const int* __restrict__ seg_live,
                                                           const float* __restrict__ S0, const float* __restrict__ z0,
-                                                          int nseg) {
+                                                          int nseg_max, const int* __restrict__ seq_start, int Hkv,
+                                                          int seg_len) {
   constexpr int kSlot = D * D + 2 * D;
   constexpr int NG = 8, U = 8;
   __shared__ float agg_a[NG][32], agg_x[NG][32];
   const int el = threadIdx.x & 31, grp = threadIdx.x >> 5;
-  const int e = blockIdx.x * 32 + el;
-  const bool live = e < D * D + D;
   const int bh = blockIdx.y;
+  // slots are laid out for the longest sequence; this head's sequence may use fewer
+  int nseg = nseg_max;
+  if (seq_start != nullptr) {
+    const int b = bh / Hkv;
+    nseg = (seq_start[b + 1] - seq_start[b] + seg_len - 1) / seg_len;
+  }
+  if (nseg < 2) return;
   {
     // No segment of this head passes anything on (every total decay is exactly zero: the usual case with gate
     // logits ~ N(0,1) and segments of hundreds of tokens): each start state is the predecessor's contribution,
     // which the output pass reads where it lies.  Nothing to do, and nothing is written.
     int any = 0;
-    for (int j = threadIdx.x; j < nseg - 1; j += 256) any |= seg_live[(size_t)bh * nseg + j];
+    for (int j = threadIdx.x; j < nseg - 1; j += 256) any |= seg_live[(size_t)bh * nseg_max + j];
     if (__syncthreads_or(any) == 0) return;
   }
-  const int c = !live ? 0 : (e < D * D ? e / D : e - D * D);
-  const int ec = live ? e : 0;
-  float* slot = ws + (size_t)bh * nseg * kSlot;
+  float* slot = ws + (size_t)bh * nseg_max * kSlot;
   const int last = nseg - 1;                 // segments 0 .. last-1 carry contributions
   const int spg = (last + NG - 1) / NG;      // segments per group
   const int sb = min(last, grp * spg), se = min(last, sb + spg);
+  // 32 state elements per round; the grid's x extent covers them in one round when there are few heads
+  // and in several when there are many (the launch stays a few thousand workgroups)
+  constexpr int kTiles = (D * D + D + 31) / 32;
+  for (int tile = blockIdx.x; tile < kTiles; tile += gridDim.x) {
+  const int e = tile * 32 + el;
+  const bool live = e < D * D + D;
+  const int c = !live ? 0 : (e < D * D ? e / D : e - D * D);
+  const int ec = live ? e : 0;
   // phase 1: (A, X) of the group from a zero start
   float A = 1.f, X = 0.f;
   for (int seg = sb; seg < se; seg += U) {
@@ -912,6 +936,8 @@ __global__ void __launch_bounds__(256) segment_scan_kernel(float* __restrict__ w
   }
   // the group that ends at the last contribution also owns the start state of the last segment
   if (live && se == last && sb < se) slot[(size_t)last * kSlot + e] = st;
+  __syncthreads();   // the partial products in LDS are free for the next round
+  }
 }
 
 // Raises the kernel's dynamic LDS limit once per device (the attribute is per device and per process); safe to
@@ -946,8 +972,10 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream, bool with_state_pa
     hipLaunchKernelGGL(k1, dim3(a.nseg - 1, heads), dim3(G::TEAM), lds1, stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(segment_scan_kernel<D>, dim3((D * D + D + 31) / 32, heads), dim3(256), 0, stream, a.ws, a.seg_live,
-                       a.S0, a.z0, a.nseg);
+    const int scan_tiles = (D * D + D + 31) / 32;
+    const int scan_x = std::min(scan_tiles, std::max(1, 2048 / heads));
+    hipLaunchKernelGGL(segment_scan_kernel<D>, dim3(scan_x, heads), dim3(256), 0, stream, a.ws, a.seg_live,
+                       a.S0, a.z0, a.nseg, a.seq_start, a.Hkv, a.seg_len);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

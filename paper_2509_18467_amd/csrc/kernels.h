@@ -86,6 +86,9 @@ struct ChunkParams {
   void* q_tail;  // nullable [B,W-1,Hq,d]  (fuse_conv only)
   void* k_tail;  // nullable [B,W-1,Hkv,d]
   void* workspace;
+  // nullable device array of B + 1 row offsets: sequences of different lengths packed along the token axis
+  // (then T is the longest length, and the tensors above hold seq_start[B] rows)
+  const int* seq_start;
   int B, T, Hq, Hkv, d, W;
   int phi;
   int fuse_conv;

@@ -21,7 +21,7 @@ CALL_CONV1D, CALL_GLA_PREFILL, CALL_GLA_STEP, CALL_LAYER_PREFILL, CALL_LAYER_PRE
 
 EXPORTS = (
     "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gate_project", "lawcat_gla_prefill", "lawcat_gla_step", "lawcat_gla_steps",
-    "lawcat_conv1d_feature", "lawcat_layer_prefill", "lawcat_layer_prefill_varlen", "lawcat_layer_prefill_fm", "lawcat_layer_prefill_static",
+    "lawcat_conv1d_feature", "lawcat_layer_prefill", "lawcat_layer_prefill_varlen", "lawcat_varlen_workspace_bytes", "lawcat_layer_prefill_fm", "lawcat_layer_prefill_static",
     "lawcat_layer_prefill_timed", "lawcat_status_string", "lawcat_version",
 )
 
@@ -75,7 +75,9 @@ def lib() -> ctypes.CDLL:
         L.lawcat_version.restype = ci
         L.lawcat_gate_project.argtypes = [dp, ci, ci] + [vp] * 6
         L.lawcat_gate_project.restype = ci
-        L.lawcat_layer_prefill_varlen.argtypes = [dp, ctypes.POINTER(ctypes.c_int32)] + [vp] * 17 + [sz, vp]
+        L.lawcat_varlen_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_int32), ci]
+        L.lawcat_varlen_workspace_bytes.restype = sz
+        L.lawcat_layer_prefill_varlen.argtypes = [dp, ctypes.POINTER(ctypes.c_int32)] + [vp] * 18 + [sz, vp]
         L.lawcat_layer_prefill_varlen.restype = ci
         L.lawcat_conv1d_feature.argtypes = [dp, ci] + [vp] * 7
         L.lawcat_conv1d_feature.restype = ci
@@ -158,21 +160,18 @@ def gate_project(desc, d_model, rank, x, w1, w2, bias, gate_logits, stream=None)
                                      _stream(stream)))
 
 
-def varlen_workspace_bytes(desc, seq_start):
-    """The largest lawcat_workspace_bytes over the sequences of a lawcat_layer_prefill_varlen call."""
-    need = 0
-    for i in range(len(seq_start) - 1):
-        one = Desc.from_buffer_copy(bytes(desc))
-        one.B, one.T = 1, int(seq_start[i + 1]) - int(seq_start[i])
-        need = max(need, workspace_bytes(one, CALL_LAYER_PREFILL))
-    return need
+def varlen_workspace_bytes(desc, seq_start, one_launch=False):
+    """Workspace bytes of a lawcat_layer_prefill_varlen call (one_launch: a device copy of the offsets is passed)."""
+    starts = (ctypes.c_int32 * len(seq_start))(*[int(v) for v in seq_start])
+    return int(lib().lawcat_varlen_workspace_bytes(ctypes.byref(desc), starts, 1 if one_launch else 0))
 
 
 def layer_prefill_varlen(desc, seq_start, Q, K, V, gate_logits, wq, wk, S0, z0, q_halo, k_halo, O, den_out, S_out, z_out,
-                         q_tail_out, k_tail_out, workspace, stream=None):
+                         q_tail_out, k_tail_out, workspace, stream=None, seq_start_dev=None):
+    """seq_start: host offsets (any int sequence); seq_start_dev: optional int32 device tensor holding the same."""
     starts = (ctypes.c_int32 * len(seq_start))(*[int(v) for v in seq_start])
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib().lawcat_layer_prefill_varlen(ctypes.byref(desc), starts, _p(Q), _p(K), _p(V), _p(gate_logits), _p(wq),
+    _check(lib().lawcat_layer_prefill_varlen(ctypes.byref(desc), starts, _p(seq_start_dev), _p(Q), _p(K), _p(V), _p(gate_logits), _p(wq),
                                              _p(wk), _p(S0), _p(z0), _p(q_halo), _p(k_halo), _p(O), _p(den_out), _p(S_out),
                                              _p(z_out), _p(q_tail_out), _p(k_tail_out), _p(workspace), nbytes,
                                              _stream(stream)))

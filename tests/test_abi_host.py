@@ -203,9 +203,9 @@ def test_varlen_entry_point_checks_every_sequence_first():
     L = lawcat.lib()
     d = lawcat.make_desc(3, 4096, 32, 8, 64)
 
-    def call(starts, desc=d, ws=A, nbytes=1 << 30, den=None, Q=A):
+    def call(starts, desc=d, ws=A, nbytes=1 << 30, den=None, Q=A, dev=None):
         arr = (ctypes.c_int32 * len(starts))(*starts)
-        return L.lawcat_layer_prefill_varlen(ctypes.byref(desc), arr, Q, A, A, A, A, A, None, None, None, None, A, den,
+        return L.lawcat_layer_prefill_varlen(ctypes.byref(desc), arr, dev, Q, A, A, A, A, A, None, None, None, None, A, den,
                                              A, A, None, None, ws, nbytes, None)
 
     assert call([1, 100, 200, 300]) == -2          # must start at 0
@@ -218,6 +218,17 @@ def test_varlen_entry_point_checks_every_sequence_first():
     assert need == lawcat.workspace_bytes(lawcat.make_desc(1, 4096, 32, 8, 64), lawcat.CALL_LAYER_PREFILL) > 0
     assert call([0, 4096, 8192, 8292], nbytes=need - 1) == -4
     assert call([0, 100, 200, 300], den=ctypes.c_void_p(0x1004)) == -5
+    # with a device copy of the offsets the batch is one set of launches: workspace as for B sequences of desc.T tokens
+    assert call([0, 100, 200, 4500], dev=A) == -2
+    assert call([0, 100, 200, 300], dev=ctypes.c_void_p(0x1002)) == -5
+    whole = lawcat.varlen_workspace_bytes(d, [0, 4096, 8192, 8292], one_launch=True)
+    assert whole > 0 and call([0, 4096, 8192, 8292], dev=A, nbytes=whole - 1) == -4
+    # segments are cut as for one sequence of all 8292 tokens (512 workgroups wanted, 8 kv heads: 64 per head,
+    # 192 tokens each: 22 + 22 + 1 segments = 360 workgroups, they fit), slots laid out for the longest sequence:
+    # 3 sequences x 8 heads x ceil(4096 / 192) slots
+    slot = (64 * 64 + 2 * 64) * 4 + 4
+    assert whole == 3 * 8 * 22 * slot
+    assert lawcat.varlen_workspace_bytes(d, [0, 4097, 8192, 9000]) == 0     # a length above desc.T
 
 
 def test_gate_project_argument_checks():

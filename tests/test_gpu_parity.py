@@ -415,11 +415,15 @@ def test_layer_prefill_with_linear_feature_map(oracle, name, T, phi, extras):
 
 
 # ------------------------------------------------------------------ sequences of different lengths, packed
+@pytest.mark.parametrize("one_launch", [False, True])
 @pytest.mark.parametrize("name,lengths", [("tiny", (5, 130, 1, 64)), ("llama1b_8k", (700, 64, 1500, 1, 333)),
-                                          ("mistral7b_16k", (257, 1024, 16))])
-def test_layer_prefill_varlen(oracle, name, lengths):
+                                          ("mistral7b_16k", (257, 1024, 16)), ("llama1b_8k", (4000, 130, 2500)),
+                                          ("llama1b_8k", tuple(37 + 11 * i for i in range(70)))])
+def test_layer_prefill_varlen(oracle, name, lengths, one_launch):
     """lawcat_layer_prefill_varlen: every sequence of the packed batch equals the oracle run on that sequence alone
-    (its own start state, conv halo, final state and conv tails)."""
+    (its own start state, conv halo, final state and conv tails) -- as one call per sequence, and as one set of
+    launches for the whole batch (device copy of the offsets; several segments per long sequence, one for the
+    short ones, 70 sequences of one segment each)."""
     base = WORKLOADS[name]
     n, total = len(lengths), sum(lengths)
     starts = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
@@ -440,8 +444,11 @@ def test_layer_prefill_varlen(oracle, name, lengths):
     z = torch.empty(n, wl.Hkv, wl.d, dtype=torch.float32, device="cuda")
     qt = torch.empty(n, wl.W - 1, wl.Hq, wl.d, dtype=dt, device="cuda")
     kt = torch.empty(n, wl.W - 1, wl.Hkv, wl.d, dtype=dt, device="cuda")
-    ws = torch.empty(max(lawcat.varlen_workspace_bytes(desc, starts), 16), dtype=torch.uint8, device="cuda")
-    lawcat.layer_prefill_varlen(desc, starts, Q, K, V, G, wq, wk, S0, z0, qh, kh, O, den, S, z, qt, kt, ws)
+    need = max(lawcat.varlen_workspace_bytes(desc, starts, one_launch), 16)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    dev_starts = torch.tensor(starts, dtype=torch.int32, device="cuda") if one_launch else None
+    lawcat.layer_prefill_varlen(desc, starts, Q, K, V, G, wq, wk, S0, z0, qh, kh, O, den, S, z, qt, kt, ws,
+                                seq_start_dev=dev_starts)
     torch.cuda.synchronize()
     o_h, den_h, S_h, z_h, qt_h, kt_h = (H.host(t) for t in (O, den, S, z, qt, kt))
     for i in range(n):
