@@ -459,7 +459,10 @@ __global__ void __launch_bounds__(D * 4, D == 64 ? 2 : 1)
     nseg = (T + a.seg_len - 1) / a.seg_len;
   }
   const int nseg_pass = OUTPUT ? nseg : nseg - 1;  // the first pass skips the last segment
-  const bool active = seg < nseg_pass;
+  // grid rows past a short sequence's last segment (packed batches) have nothing to do; the whole team leaves
+  // before the first barrier
+  if (seg >= nseg_pass) return;
+  constexpr bool active = true;
   const int s0 = seg * a.seg_len;
   const int s1 = active ? min(T, s0 + a.seg_len) : s0;
 
