@@ -59,3 +59,34 @@ def test_repeated_calls_are_bit_identical(d, group, mode):
                 same = torch.equal(_bits(cur[name]), _bits(first[name]))
                 assert same, (f"d={d} group={group} {mode} B={B} T={T}: {name} of call {it} differs from call 0 in "
                               f"{int((_bits(cur[name]) != _bits(first[name])).sum())} elements")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_matrix_core_side_kernels_are_bit_identical(d):
+    """The conv + feature-matrix kernel and the gate projection reduce in a fixed order too (the gate projection
+    adds its four partial sums in wave order): repeated calls agree bit for bit, at a size with several
+    workgroups per compute unit and the 32-token workgroups of the gate kernel."""
+    from paper_2509_18467_amd.inputs import make_feature_weights, make_gate_inputs
+
+    wl = Workload("det_side", B=1, T=16400, Hq=32, Hkv=8, d=d)
+    dt = torch.bfloat16
+    x = make_inputs(wl, seed=5, halo=True)
+    dm = 2048 if d == 64 else 4096
+    gi = make_gate_inputs(wl, dm, 32, seed=5)
+    desc = H.desc_for(wl, feature_map=1)
+    Q, wq, qh = H.dev(x["Q"], dt), H.dev(x["wq"], dt), H.dev(x["q_halo"], dt)
+    wf = H.dev(make_feature_weights(wl, seed=5), dt)
+    gx, gw1, gw2, gb = (H.dev(gi[k], dt) for k in ("x", "w1", "w2", "bias"))
+    first = None
+    for it in range(RUNS):
+        y = torch.empty_like(Q)
+        g = torch.empty(wl.B, wl.T, wl.Hkv, d, dtype=dt, device="cuda")
+        lawcat.conv1d_feature(desc, wl.Hq, Q, wq, wf, qh, y, None)
+        lawcat.gate_project(desc, dm, 32, gx, gw1, gw2, gb, g)
+        torch.cuda.synchronize()
+        cur = {"feature": y, "gate": g}
+        if first is None:
+            first = cur
+            continue
+        for name in cur:
+            assert torch.equal(_bits(cur[name]), _bits(first[name])), f"d={d}: {name} of call {it} differs from call 0"
