@@ -5,16 +5,14 @@
 // (26 flop/B at dm = 2048, N = 512), so the matrix cores are used for what they are, a dense contraction, and
 // the kernel is laid out around the reads of x.
 //   bf16 storage, rank 32: both products transposed so that no operand is ever shuffled,
-//     H^T = W1 x^T   (A = 16 rows of w1, B = 16 tokens of x, read straight from memory in fragment layout:
-//                     the four lane groups of a row read 64 contiguous bytes per MFMA),
+//     H^T = W1 x^T   (A = 16 rows of w1, read from L2 in fragment layout; B = 16 tokens of x, read from HBM as whole
+//                     row pieces and turned into fragment layout through the wave's own LDS rows),
 //     G^T = W2 H^T   (the two accumulator tiles of H^T, rounded to bf16, ARE the B operand: k slot s < 4 is
 //                     rank 4g + s, slot s >= 4 rank 16 + 4g + s - 4; w2 rows are read with the same permutation),
 //     a lane then holds 4 adjacent channels of one token; they pass through the wave's own LDS rows and leave
-//     as whole 256-byte row pieces.  The four waves of a workgroup share 16 tokens and split the channels of
-//     both products.
+//     as whole 256-byte row pieces.  The four waves of a workgroup share 16 or 32 tokens and split the channels
+//     of both products.
 //   anything else (fp32 storage, other ranks): one workgroup per token, plain fp32 FMAs.
-#include <mutex>
-
 #include "kernels.h"
 
 namespace lawcat {
