@@ -976,7 +976,8 @@ hipError_t launch_all(const ChunkArgs& a, hipStream_t stream, bool with_state_pa
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int scan_tiles = (D * D + D + 31) / 32;
-    const int scan_x = std::min(scan_tiles, std::max(1, 2048 / heads));
+    // one workgroup per 32 state elements and head, unless that is more than a few thousand workgroups
+    const int scan_x = (long long)scan_tiles * heads <= 8192 ? scan_tiles : std::max(1, 4096 / heads);
     hipLaunchKernelGGL(segment_scan_kernel<D>, dim3(scan_x, heads), dim3(256), 0, stream, a.ws, a.seg_live,
                        a.S0, a.z0, a.nseg, a.seq_start, a.Hkv, a.seg_len);
     e = hipGetLastError();
