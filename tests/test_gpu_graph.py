@@ -128,3 +128,43 @@ def test_projection_feature_map_layer_and_decode_block_in_one_graph():
             view = torch.int16 if a.dtype == dt else torch.int32
             assert torch.equal(a.view(view), b.view(view)), f"replay {rep}: {k} differs"
         assert torch.isfinite(gbuf["on"].float()).all() and torch.isfinite(gbuf["S"]).all()
+
+
+def test_two_streams_with_their_own_workspaces_do_not_interfere():
+    """The library keeps no state between calls (every scratch byte is in the caller's workspace), so two calls
+    enqueued on different streams with different workspaces may overlap on the GPU; each must reproduce what it
+    gives alone, bit for bit."""
+    wl = WORKLOADS["llama1b_8k"].with_T(3000)
+    dt = torch.bfloat16
+    desc = H.desc_for(wl, feature_map=1)
+    xs = [make_inputs(wl, seed=70 + i) for i in range(2)]
+    dev = [{n: H.dev(x[n], dt) for n in ("Q", "K", "V", "G", "wq", "wk")} for x in xs]
+    wss = [lawcat.alloc_workspace(desc, lawcat.CALL_LAYER_PREFILL) for _ in range(2)]
+
+    def outputs():
+        return (torch.empty_like(dev[0]["Q"]), torch.empty(wl.B, wl.Hkv, wl.d, wl.d, device="cuda"),
+                torch.empty(wl.B, wl.Hkv, wl.d, device="cuda"))
+
+    def call(i, out, stream=None):
+        d = dev[i]
+        lawcat.layer_prefill(desc, d["Q"], d["K"], d["V"], d["G"], d["wq"], d["wk"], None, None, None, None,
+                             out[0], None, out[1], out[2], None, None, wss[i], stream=stream)
+
+    alone = [outputs(), outputs()]
+    for i in range(2):
+        call(i, alone[i])
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(5):
+        both = [outputs(), outputs()]
+        for t in both[0] + both[1]:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        for i in range(2):
+            call(i, both[i], stream=streams[i])
+        for s in streams:
+            s.synchronize()
+        for i in range(2):
+            for got, ref, what in zip(both[i], alone[i], ("o", "S", "z")):
+                view = torch.int16 if got.dtype == dt else torch.int32
+                assert torch.equal(got.view(view), ref.view(view)), f"rep {rep}, stream {i}: {what} differs"
