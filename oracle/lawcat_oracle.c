@@ -190,6 +190,158 @@ void lawcat_oracle_gla_prefill(int B, int T, int Hq, int Hkv, int dk, int dv, co
     }
 }
 
+/*
+ * Adjoint of lawcat_oracle_gla_prefill (what the layer-wise distillation of section 5 differentiates through):
+ * given dO = dL/do, the gradients with respect to q, k, v, the gate logits and the start state.  Token by token:
+ * the forward recurrence first, every state kept ([T+1, dk, dv+1] doubles per kv head: small cases only), then
+ * backwards with Gr_t = dL/d[S_t | z_t]:
+ *   num = q S_t, den = q z_t + eps, o = num / den     =>  dnum = dO / den,  dden = -(dO . o) / den
+ *   dq_t  = S_t dnum^T + z_t dden
+ *   Gr_t  = alpha_{t+1} (.) Gr_{t+1}  +  sum over the group's query heads of  q_t^T [dnum | dden]
+ *   dk_t  = Gr_t [v_t | 1]^T,   dv_t = k_t Gr_t[:, :dv]
+ *   dalpha_t[c] = sum_j Gr_t[c, j] [S_{t-1} | z_{t-1}][c, j],   alpha = sigmoid(g)^gate_scale
+ *   dg_t  = dalpha_t * gate_scale * alpha_t * (1 - sigmoid(g_t))
+ *   dS0, dz0 = alpha_1 (.) Gr_1 (the gradient that reaches the start state)
+ * Shapes as in lawcat_oracle_gla_prefill; dS0 [B,Hkv,dk,dv], dz0 [B,Hkv,dk].
+ */
+void lawcat_oracle_gla_backward(int B, int T, int Hq, int Hkv, int dk, int dv, const double* q, const double* k,
+                                const double* v, const double* g, double gate_scale, double eps, const double* S0,
+                                const double* z0, const double* dO, double* dq, double* dkk, double* dvv, double* dg,
+                                double* dS0, double* dz0) {
+  const int group = Hq / Hkv;
+  const int w = dv + 1; /* columns of the augmented state [S | z] */
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int b = 0; b < B; ++b)
+    for (int hk = 0; hk < Hkv; ++hk) {
+      const size_t sidx = ((size_t)b * Hkv + hk);
+      double* St = (double*)malloc(sizeof(double) * (size_t)(T + 1) * dk * w); /* St[t+1] = state after token t */
+      double* al = (double*)malloc(sizeof(double) * (size_t)T * dk);
+      double* Gr = (double*)calloc((size_t)dk * w, sizeof(double));
+      double* dhat = (double*)malloc(sizeof(double) * (size_t)w);
+      for (int c = 0; c < dk; ++c) {
+        for (int j = 0; j < dv; ++j) St[(size_t)c * w + j] = S0 ? S0[(sidx * dk + c) * dv + j] : 0.0;
+        St[(size_t)c * w + dv] = z0 ? z0[sidx * dk + c] : 0.0;
+      }
+      for (int t = 0; t < T; ++t) {
+        const double* kt = k + (((size_t)b * T + t) * Hkv + hk) * dk;
+        const double* gt = g + (((size_t)b * T + t) * Hkv + hk) * dk;
+        const double* vt = v + (((size_t)b * T + t) * Hkv + hk) * dv;
+        const double* prev = St + (size_t)t * dk * w;
+        double* cur = St + (size_t)(t + 1) * dk * w;
+        for (int c = 0; c < dk; ++c) {
+          const double a = exp(gate_scale * log_sigmoid(gt[c]));
+          al[(size_t)t * dk + c] = a;
+          for (int j = 0; j < dv; ++j) cur[(size_t)c * w + j] = a * prev[(size_t)c * w + j] + kt[c] * vt[j];
+          cur[(size_t)c * w + dv] = a * prev[(size_t)c * w + dv] + kt[c];
+        }
+      }
+      for (int t = T - 1; t >= 0; --t) {
+        const double* kt = k + (((size_t)b * T + t) * Hkv + hk) * dk;
+        const double* gt = g + (((size_t)b * T + t) * Hkv + hk) * dk;
+        const double* vt = v + (((size_t)b * T + t) * Hkv + hk) * dv;
+        const double* cur = St + (size_t)(t + 1) * dk * w;
+        const double* prev = St + (size_t)t * dk * w;
+        /* every query head of the group: its own dq, and its share of Gr_t */
+        for (int r = 0; r < group; ++r) {
+          const int hq = hk * group + r;
+          const double* qt = q + (((size_t)b * T + t) * Hq + hq) * dk;
+          const double* dot = dO + (((size_t)b * T + t) * Hq + hq) * dv;
+          double* dqt = dq + (((size_t)b * T + t) * Hq + hq) * dk;
+          double den = eps;
+          for (int c = 0; c < dk; ++c) den += qt[c] * cur[(size_t)c * w + dv];
+          double dden = 0.0;
+          for (int j = 0; j < dv; ++j) {
+            double num = 0.0;
+            for (int c = 0; c < dk; ++c) num += qt[c] * cur[(size_t)c * w + j];
+            dhat[j] = dot[j] / den;
+            dden -= dot[j] * (num / den) / den;
+          }
+          dhat[dv] = dden;
+          for (int c = 0; c < dk; ++c) {
+            double acc = 0.0;
+            for (int j = 0; j < w; ++j) {
+              acc += cur[(size_t)c * w + j] * dhat[j];
+              Gr[(size_t)c * w + j] += qt[c] * dhat[j];
+            }
+            dqt[c] = acc;
+          }
+        }
+        double* dkt = dkk + (((size_t)b * T + t) * Hkv + hk) * dk;
+        double* dvt = dvv + (((size_t)b * T + t) * Hkv + hk) * dv;
+        double* dgt = dg + (((size_t)b * T + t) * Hkv + hk) * dk;
+        for (int j = 0; j < dv; ++j) dvt[j] = 0.0;
+        for (int c = 0; c < dk; ++c) {
+          double acc = Gr[(size_t)c * w + dv]; /* the column of ones */
+          double dal = Gr[(size_t)c * w + dv] * prev[(size_t)c * w + dv];
+          for (int j = 0; j < dv; ++j) {
+            acc += Gr[(size_t)c * w + j] * vt[j];
+            dvt[j] += kt[c] * Gr[(size_t)c * w + j];
+            dal += Gr[(size_t)c * w + j] * prev[(size_t)c * w + j];
+          }
+          dkt[c] = acc;
+          const double a = al[(size_t)t * dk + c];
+          const double sg = exp(log_sigmoid(gt[c]));
+          dgt[c] = dal * gate_scale * a * (1.0 - sg);
+          /* what flows on to token t-1 */
+          for (int j = 0; j < w; ++j) Gr[(size_t)c * w + j] *= a;
+        }
+      }
+      for (int c = 0; c < dk; ++c) {
+        for (int j = 0; j < dv; ++j) dS0[(sidx * dk + c) * dv + j] = Gr[(size_t)c * w + j];
+        dz0[sidx * dk + c] = Gr[(size_t)c * w + dv];
+      }
+      free(St);
+      free(al);
+      free(Gr);
+      free(dhat);
+    }
+}
+
+/*
+ * Adjoint of lawcat_oracle_conv1d_causal: with y = phi(u), u[t,c] = sum_delta w[c,delta] x[t-delta,c] (rows before
+ * the first token from the halo), given dy:
+ *   du = dy * phi'(u)  (1 for the identity; 1 for u > 0 and exp(u) otherwise for 1 + ELU)
+ *   dx[t] = sum_delta w[delta] du[t+delta]   (dhalo likewise for the rows before the first token)
+ *   dw[h,c,delta] = sum over batch and tokens of du[t] x[t-delta]
+ * dhalo may be NULL (and is ignored when halo is NULL).
+ */
+void lawcat_oracle_conv1d_backward(int B, int T, int H, int d, int W, const double* x, const double* wt,
+                                   const double* halo, int phi, const double* dy, double* dx, double* dw,
+                                   double* dhalo) {
+  const size_t row = (size_t)H * d;
+  for (size_t i = 0; i < (size_t)B * T * row; ++i) dx[i] = 0.0;
+  for (size_t i = 0; i < row * W; ++i) dw[i] = 0.0;
+  if (dhalo && halo)
+    for (size_t i = 0; i < (size_t)B * (W - 1) * row; ++i) dhalo[i] = 0.0;
+  for (int b = 0; b < B; ++b)
+    for (int t = 0; t < T; ++t)
+      for (int h = 0; h < H; ++h)
+        for (int c = 0; c < d; ++c) {
+          const size_t e = (size_t)h * d + c;
+          double u = 0.0;
+          for (int dl = 0; dl < W; ++dl) {
+            const int s = t - dl;
+            double xv = 0.0;
+            if (s >= 0) xv = x[((size_t)b * T + s) * row + e];
+            else if (halo) xv = halo[((size_t)b * (W - 1) + (W - 1 + s)) * row + e];
+            u += wt[e * W + dl] * xv;
+          }
+          const double du = dy[((size_t)b * T + t) * row + e] * (phi == 1 ? (u > 0.0 ? 1.0 : exp(u)) : 1.0);
+          for (int dl = 0; dl < W; ++dl) {
+            const int s = t - dl;
+            double xv = 0.0;
+            if (s >= 0) {
+              xv = x[((size_t)b * T + s) * row + e];
+              dx[((size_t)b * T + s) * row + e] += wt[e * W + dl] * du;
+            } else if (halo) {
+              xv = halo[((size_t)b * (W - 1) + (W - 1 + s)) * row + e];
+              if (dhalo) dhalo[((size_t)b * (W - 1) + (W - 1 + s)) * row + e] += wt[e * W + dl] * du;
+            }
+            dw[e * W + dl] += du * xv;
+          }
+        }
+}
+
 int lawcat_oracle_max_threads(void) {
 #ifdef _OPENMP
   extern int omp_get_max_threads(void);

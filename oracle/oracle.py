@@ -45,6 +45,10 @@ def _load():
         _lib.lawcat_oracle_feature_linear.restype = None
         _lib.lawcat_oracle_gate_project.argtypes = [ctypes.c_int] * 5 + [dp, dp, dp, dp, dp]
         _lib.lawcat_oracle_gate_project.restype = None
+        _lib.lawcat_oracle_gla_backward.argtypes = ([ctypes.c_int] * 6 + [dp] * 4 + [ctypes.c_double] * 2 + [dp] * 9)
+        _lib.lawcat_oracle_gla_backward.restype = None
+        _lib.lawcat_oracle_conv1d_backward.argtypes = [ctypes.c_int] * 5 + [dp, dp, dp, ctypes.c_int, dp, dp, dp, dp]
+        _lib.lawcat_oracle_conv1d_backward.restype = None
         _lib.lawcat_oracle_max_threads.restype = ctypes.c_int
     return _lib
 
@@ -130,6 +134,37 @@ def gla_prefill(q, k, v, g, gate_scale: float = 1.0, eps: float = 0.0, S0=None, 
         _ptr(S0), _ptr(z0), _ptr(o), _ptr(den), _ptr(num), _ptr(S), _ptr(z),
     )
     return {"o": o, "den": den, "num": num, "S": S, "z": z}
+
+
+def gla_backward(q, k, v, g, dO, gate_scale: float = 1.0, eps: float = 0.0, S0=None, z0=None):
+    """Adjoint of gla_prefill: gradients of a loss with dL/do = dO with respect to q, k, v, the gate logits and the
+    start state.  Keeps every state of the forward recurrence: small cases only."""
+    lib = _load()
+    q, k, v, g, dO = (_f64(a) for a in (q, k, v, g, dO))
+    B, T, Hq, dk = q.shape
+    Hkv, dv = v.shape[2], v.shape[3]
+    S0 = None if S0 is None else _f64(S0)
+    z0 = None if z0 is None else _f64(z0)
+    out = {"dq": np.empty_like(q), "dk": np.empty_like(k), "dv": np.empty_like(v), "dg": np.empty_like(g),
+           "dS0": np.empty((B, Hkv, dk, dv)), "dz0": np.empty((B, Hkv, dk))}
+    lib.lawcat_oracle_gla_backward(B, T, Hq, Hkv, dk, dv, _ptr(q), _ptr(k), _ptr(v), _ptr(g), float(gate_scale), float(eps),
+                                   _ptr(S0), _ptr(z0), _ptr(dO), _ptr(out["dq"]), _ptr(out["dk"]), _ptr(out["dv"]),
+                                   _ptr(out["dg"]), _ptr(out["dS0"]), _ptr(out["dz0"]))
+    return out
+
+
+def conv1d_backward(x, w, dy, halo=None, feature_map: int = 0):
+    """Adjoint of conv1d_causal: returns dict(dx, dw, dhalo)."""
+    lib = _load()
+    x, w, dy = _f64(x), _f64(w), _f64(dy)
+    B, T, H, d = x.shape
+    W = w.shape[-1]
+    halo = None if halo is None or W == 1 else _f64(halo)
+    dx, dw = np.empty_like(x), np.empty_like(w)
+    dhalo = None if halo is None else np.empty_like(halo)
+    lib.lawcat_oracle_conv1d_backward(B, T, H, d, W, _ptr(x), _ptr(w), _ptr(halo), int(feature_map), _ptr(dy), _ptr(dx),
+                                      _ptr(dw), _ptr(dhalo))
+    return {"dx": dx, "dw": dw, "dhalo": dhalo}
 
 
 def gla_step(q, k, v, g, S, z, gate_scale: float = 1.0, eps: float = 0.0):

@@ -339,6 +339,77 @@ def test_gate_projection_two_low_rank_layers(oracle):
     np.testing.assert_allclose(r1["S"], S, rtol=1e-12, atol=1e-12)
 
 
+def _fd(f, x, h=1e-6):
+    """Central finite differences of the scalar function f with respect to every entry of x (fp64)."""
+    gr = np.zeros_like(x)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        old = x[i]
+        x[i] = old + h
+        fp = f()
+        x[i] = old - h
+        fm = f()
+        x[i] = old
+        gr[i] = (fp - fm) / (2 * h)
+    return gr
+
+
+@pytest.mark.parametrize("gate_scale,eps,start", [(1.0, 0.0, False), (0.6, 0.3, True)])
+def test_adjoint_of_the_recurrence_against_finite_differences(oracle, gate_scale, eps, start):
+    """gla_backward is the adjoint of gla_prefill: for a loss L = sum(w * o) every gradient equals the central
+    finite difference of the FORWARD oracle (grouped heads, a start state, gate_scale and eps away from their
+    defaults); and with all gates open and v = dO = 1 the closed form dq_t = 0 (o is then 1 whatever q is)."""
+    rng = np.random.default_rng(41)
+    B, T, Hq, Hkv, d = 1, 6, 4, 2, 3
+    q = np.abs(_rand(rng, B, T, Hq, d)) + 0.2
+    k = np.abs(_rand(rng, B, T, Hkv, d)) + 0.2
+    v, g = _rand(rng, B, T, Hkv, d), _rand(rng, B, T, Hkv, d)
+    S0 = _rand(rng, B, Hkv, d, d) if start else None
+    z0 = np.abs(_rand(rng, B, Hkv, d)) + 0.5 if start else None
+    w = _rand(rng, B, T, Hq, d)
+
+    def loss():
+        return float((oracle.gla_prefill(q, k, v, g, gate_scale, eps, S0, z0)["o"] * w).sum())
+
+    got = oracle.gla_backward(q, k, v, g, w, gate_scale, eps, S0, z0)
+    for name, x in (("dq", q), ("dk", k), ("dv", v), ("dg", g)):
+        np.testing.assert_allclose(got[name], _fd(loss, x), rtol=2e-6, atol=2e-8, err_msg=name)
+    if start:
+        np.testing.assert_allclose(got["dS0"], _fd(loss, S0), rtol=2e-6, atol=2e-8, err_msg="dS0")
+        np.testing.assert_allclose(got["dz0"], _fd(loss, z0), rtol=2e-6, atol=2e-8, err_msg="dz0")
+    # every output is the same weighted average of ones: it does not depend on q, k or the gates at all
+    ones = np.ones_like(v)
+    flat = oracle.gla_backward(q, k, ones, g, w)
+    for name in ("dq", "dk", "dg"):
+        assert np.abs(flat[name]).max() < 1e-12, name
+    # and dv of that case: o_t = sum_i p_ti v_i with weights p that sum to one, so the dv_i of a loss sum(o) sum to T * group
+    tot = oracle.gla_backward(q, k, v, g, np.ones_like(w))["dv"]
+    np.testing.assert_allclose(tot.sum(axis=1), np.full((B, Hkv, d), T * (Hq // Hkv)), rtol=1e-12)
+
+
+@pytest.mark.parametrize("phi,halo", [(0, False), (1, True)])
+def test_adjoint_of_the_conv_against_finite_differences(oracle, phi, halo):
+    rng = np.random.default_rng(43)
+    B, T, H, d, W = 2, 7, 2, 3, 4
+    x, wt, dy = _rand(rng, B, T, H, d), _rand(rng, H, d, W), _rand(rng, B, T, H, d)
+    hl = _rand(rng, B, W - 1, H, d) if halo else None
+
+    def loss():
+        return float((oracle.conv1d_causal(x, wt, hl, phi) * dy).sum())
+
+    got = oracle.conv1d_backward(x, wt, dy, hl, phi)
+    np.testing.assert_allclose(got["dx"], _fd(loss, x), rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(got["dw"], _fd(loss, wt), rtol=2e-6, atol=2e-8)
+    if halo:
+        np.testing.assert_allclose(got["dhalo"], _fd(loss, hl), rtol=2e-6, atol=2e-8)
+    else:
+        assert got["dhalo"] is None
+    # an impulse kernel is the identity, and so is its adjoint
+    imp = np.zeros_like(wt); imp[..., 0] = 1.0
+    np.testing.assert_array_equal(oracle.conv1d_backward(x, imp, dy, None, 0)["dx"], dy)
+
+
 def test_continuation_split_prefill_and_steps(oracle):
     """prefill(T) == prefill(T1) then prefill(T-T1) with carried (S, z, conv tails) == T single steps."""
     rng = np.random.default_rng(12)
