@@ -2,10 +2,10 @@
 // query and the key,
 //   y[b,t,h,f] = phi( sum_c x~[b,t,h,c] * Wf[h / group, c, f] ),   x~ = causal depthwise conv of x (no phi)
 // fused with that conv: one kernel reads the raw rows, slides the conv window in registers, keeps the conv
-// output of a 64-token tile in LDS and multiplies it by the head's d x d matrix.
+// output of a tile in LDS and multiplies it by the head's d x d matrix.
 //   bf16 storage: the product runs on the matrix cores (v_mfma_f32_16x16x32_bf16, fp32 accumulate), computed
-//     transposed (y^T = Wf^T x~^T) so that a lane ends up with four adjacent features of one token and stores
-//     8 bytes; the conv output is rounded to bf16 once, as an MFMA operand.
+//     transposed (y^T = Wf^T x~^T) so that a lane ends up with four adjacent features of one token; the results
+//     go back through LDS and leave as whole rows; the conv output is rounded to bf16 once, as an MFMA operand.
 //   fp32 storage: plain fp32 FMAs (the 1e-4 bar leaves no room for bf16 operands).
 // Streaming and HBM-bound: 2 bytes read and 2 written per element; the matrix (8 or 32 KB) is read from L2 once
 // per workgroup, which walks a run of tiles.
@@ -20,7 +20,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kTile = 64;        // tokens per tile
+constexpr int kTile = 64;        // fp32 kernel: tokens per tile
 constexpr int kTilesPerBlock = 4;
 
 typedef unsigned int u32x4 __attribute__((vector_size(16)));
@@ -34,7 +34,7 @@ __device__ inline uint32_t pack2(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-// ---- conv of one 64-token tile into LDS (no phi).  Thread = one channel pair x a run of tokens.
+// ---- fp32 kernel: conv of one 64-token tile into LDS (no phi).  Thread = one channel pair x a run of tokens.
 // xs: [kTile][D] elements of XS (bf16_t packed pairs or float), row stride `rs` bytes.
 template <typename T, int D>
 __device__ inline void conv_tile(const T* __restrict__ x, const T* __restrict__ w, const T* __restrict__ halo, int b,
