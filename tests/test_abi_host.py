@@ -244,3 +244,34 @@ def test_gate_project_argument_checks():
     assert call(dm=16384) == -3                     # a row of x plus the intermediate must fit 64 KB of LDS as fp32
     assert call(bias=ctypes.c_void_p(0x1008)) == -5
     assert call(desc=lawcat.make_desc(1, 0, 32, 8, 64)) == -2
+
+
+def test_packed_batch_plan_fits_the_chip_in_one_round():
+    """The one-launch plan of a packed batch: the workspace grows with the longest sequence only through its segment
+    count, many short sequences get one segment each, and lengthening the segments keeps the workgroups within
+    the 512 (head dim 64) or 256 (128) the chip holds at once -- read off the workspace size, which is
+    sequences x kv heads x segments-of-the-longest x slot bytes."""
+    def slots_of(d, starts, **kw):
+        desc = lawcat.make_desc(len(starts) - 1, max(b - a for a, b in zip(starts, starts[1:])), 32, 8, d, **kw)
+        need = lawcat.varlen_workspace_bytes(desc, starts, one_launch=True)
+        slot = (d * d + 2 * d) * 4 + 4
+        assert need % ((len(starts) - 1) * 8 * slot) == 0
+        return need // ((len(starts) - 1) * 8 * slot)        # segments of the longest sequence (0: one segment each)
+
+    def cum(lengths):
+        out = [0]
+        for n in lengths:
+            out.append(out[-1] + n)
+        return out
+
+    # 24 sequences, 32768 tokens: 512-token segments would give 544 workgroups; 640-token ones give 512
+    mix = [4096, 2048, 1024, 512, 256, 256] * 4
+    assert slots_of(64, cum(mix)) == 7                        # ceil(4096 / 640)
+    # one long sequence behaves as lawcat_layer_prefill does
+    assert slots_of(64, [0, 32768]) == 64
+    # 100 short sequences: more (sequence, head) pairs than places, one segment each, no workspace
+    assert slots_of(64, cum([300] * 100)) == 0
+    # head dim 128: 256 places
+    assert slots_of(128, [0, 16384]) == 32
+    # an explicit segment length is taken as given
+    assert slots_of(64, cum(mix), segment=256) == 16
