@@ -291,7 +291,32 @@ def run_side_ops(wl, steps=30):
     e1.record()
     torch.cuda.synchronize()
     block_us = e0.elapsed_time(e1) / (10 * nb) * 1e3
-    return {"gla_steps_block256": {"us_per_step": block_us},
+    # the attention's backward (fp32 vector arithmetic, a first version): one call at the headline shape
+    dq_, dk_ = (torch.randn(wl.B, wl.T, h, wl.d, device="cuda").abs().to(dt) for h in (wl.Hq, wl.Hkv))
+    dv_ = torch.randn(wl.B, wl.T, wl.Hkv, wl.d, device="cuda").to(dt)
+    dg_ = (4.0 + torch.randn(wl.B, wl.T, wl.Hkv, wl.d, device="cuda")).to(dt)
+    dplain = lawcat.make_desc(wl.B, wl.T, wl.Hq, wl.Hkv, wl.d, conv_width=wl.W, dtype=lawcat.DTYPE_BF16)
+    do_, dden_ = torch.empty_like(dq_), torch.empty(wl.B, wl.T, wl.Hq, device="cuda")
+    wsf = lawcat.alloc_workspace(dplain, lawcat.CALL_GLA_PREFILL)
+    lawcat.gla_prefill(dplain, dq_, dk_, dv_, dg_, None, None, do_, dden_,
+                       torch.empty(wl.B, wl.Hkv, wl.d, wl.d, device="cuda"), torch.empty(wl.B, wl.Hkv, wl.d, device="cuda"), wsf)
+    dO_ = torch.randn(wl.B, wl.T, wl.Hq, wl.d, device="cuda").to(dt)
+    grads = [torch.empty_like(t) for t in (dq_, dk_, dv_, dg_)]
+    wsb = lawcat.alloc_workspace(dplain, lawcat.CALL_GLA_BACKWARD)
+    for _ in range(2):
+        lawcat.gla_backward(dplain, dq_, dk_, dv_, dg_, dden_, dO_, None, None, *grads, None, None, wsb)
+    e0.record()
+    for _ in range(5):
+        lawcat.gla_backward(dplain, dq_, dk_, dv_, dg_, dden_, dO_, None, None, *grads, None, None, wsb)
+    e1.record()
+    torch.cuda.synchronize()
+    bwd_ms = e0.elapsed_time(e1) / 5
+    # multiply-adds on the d x (d + 1) state: both sweeps update it once per token and kv head and read it once per
+    # query head (dq; q^T d^), plus dk and dv: 2 * (2 + 2 * group + 2) * d * d per token and kv head, sweeps run twice
+    bwd_flops = 2.0 * wl.B * wl.T * wl.Hkv * wl.d * wl.d * (4 + 2 * wl.Hq // wl.Hkv)
+    return {"gla_backward": {"ms": bwd_ms, "tokens_per_s": wl.B * wl.T / (bwd_ms * 1e-3),
+                             "fp32_TFLOP/s_outputs_only": bwd_flops / (bwd_ms * 1e-3) / 1e12},
+            "gla_steps_block256": {"us_per_step": block_us},
             "gla_step_batch256": {"us_per_step": batch_us, "state_bytes_per_step": batch_bytes,
                                   "GB/s": batch_bytes / (batch_us * 1e-6) / 1e9,
                                   "frac_of_hbm_peak": batch_bytes / (batch_us * 1e-6) / 1e9 / HBM_PEAK_GBS},

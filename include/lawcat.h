@@ -70,7 +70,8 @@ enum {
   LAWCAT_CALL_GLA_PREFILL = 1,
   LAWCAT_CALL_GLA_STEP = 2,
   LAWCAT_CALL_LAYER_PREFILL = 3,
-  LAWCAT_CALL_LAYER_PREFILL_FM = 4
+  LAWCAT_CALL_LAYER_PREFILL_FM = 4,
+  LAWCAT_CALL_GLA_BACKWARD = 5
 };
 
 typedef struct lawcat_desc {
@@ -141,6 +142,25 @@ LAWCAT_API int lawcat_gla_prefill(const lawcat_desc* desc, const void* q, const 
                        const void* gate_logits, const float* S0, const float* z0, void* o,
                        float* den_out, float* S_out, float* z_out, void* workspace,
                        size_t workspace_bytes, void* stream);
+
+/*
+ * Adjoint of lawcat_gla_prefill (section 5 trains the layer by gradient descent on a layer-wise loss): given
+ * dO = dL/dO and the forward's den_out, the gradients with respect to q, k, v, the gate logits and the start
+ * state.  With v^ = [v, 1], S^ = [S | z], dnum = dO / den, dden = -(q_t S_t dnum^T) / den, d^ = [dnum | dden]:
+ *   dq_t = S^_t d^_t^T;   Gr_t = alpha_{t+1} (.) Gr_{t+1} + sum over the group's query heads of q_t^T d^_t;
+ *   dk_t = Gr_t v^_t^T;   dv_t = k_t Gr_t[:, :dv];
+ *   dgate_logits_t = gate_scale (1 - sigmoid(g_t)) sum_{s >= t} ( sum_h q_s (.) dq_s - k_s (.) dk_s ).
+ *   q, k, v, gate_logits, S0, z0 as lawcat_gla_prefill took them; den [B,T,Hq] as it returned it (den_out; the
+ *   output O itself is not needed);  dO [B,T,Hq,dv];  dq, dk, dv, dgate_logits: shapes and type of q, k, v,
+ *   gate_logits;  dS0 [B,Hkv,dk,dv], dz0 [B,Hkv,dk]: nullable.  Workspace: LAWCAT_CALL_GLA_BACKWARD.
+ * fp32 vector arithmetic throughout (both storage types), parallel over (batch, kv head) and segments of the
+ * sequence; a first version, several times the forward's time.  More than 16 query heads per kv head (fewer at
+ * head dim 128, where the staging of a token must fit LDS) is LAWCAT_E_UNSUPPORTED.
+ */
+LAWCAT_API int lawcat_gla_backward(const lawcat_desc* desc, const void* q, const void* k, const void* v,
+                        const void* gate_logits, const float* den, const void* dO,
+                        const float* S0, const float* z0, void* dq, void* dk, void* dv, void* dgate_logits,
+                        float* dS0, float* dz0, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Section 4.2, one recurrent (decode) step on one token per sequence; desc->T is ignored.

@@ -99,6 +99,10 @@ size_t workspace_bytes_checked(const lawcat_desc* d, int which) {
       return align_up(rows * d->Hq * d->dk * elem_bytes(d), 256) + align_up(rows * d->Hkv * d->dk * elem_bytes(d), 256) +
              align_up(inner, 256);
     }
+    case LAWCAT_CALL_GLA_BACKWARD: {
+      const ChunkPlan plan = plan_for(d);
+      return gla_backward_workspace_bytes(d->B, d->T, d->Hq, d->Hkv, d->dk, plan.seg_len, plan.nseg);
+    }
     default:
       return 0;
   }
@@ -176,6 +180,30 @@ int lawcat_conv1d_feature(const lawcat_desc* desc, int n_heads, const void* x, c
   hipStream_t hs = static_cast<hipStream_t>(stream);
   if (launch_conv_feature(p, wf, n_heads / desc->Hkv, hs) != hipSuccess) return LAWCAT_E_HIP;
   return hip_status(launch_conv_tail(p, hs));
+}
+
+int lawcat_gla_backward(const lawcat_desc* desc, const void* q, const void* k, const void* v, const void* gate_logits,
+                        const float* den, const void* dO, const float* S0, const float* z0, void* dq,
+                        void* dk, void* dv, void* dgate_logits, float* dS0, float* dz0, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (!gla_backward_supports(desc->dk, desc->Hq / desc->Hkv) || (uint64_t)desc->B * desc->Hkv > 65535) return LAWCAT_E_UNSUPPORTED;
+  if (!q || !k || !v || !gate_logits || !den || !dO || !dq || !dk || !dv || !dgate_logits) return LAWCAT_E_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(gate_logits) || !aligned16(den) ||
+      !aligned16(dO) || !aligned16(S0) || !aligned16(z0) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) ||
+      !aligned16(dgate_logits) || !aligned16(dS0) || !aligned16(dz0) || !aligned16(workspace))
+    return LAWCAT_E_ALIGN;
+  const size_t need = workspace_bytes_checked(desc, LAWCAT_CALL_GLA_BACKWARD);
+  if (workspace == nullptr || workspace_bytes < need) return LAWCAT_E_WORKSPACE;
+  const ChunkPlan plan = plan_for(desc);
+  GlaBackwardParams p{};
+  p.q = q; p.k = k; p.v = v; p.g = gate_logits; p.den = den; p.dO = dO; p.S0 = S0; p.z0 = z0;
+  p.dq = dq; p.dk = dk; p.dv = dv; p.dg = dgate_logits; p.dS0 = dS0; p.dz0 = dz0; p.workspace = workspace;
+  p.B = desc->B; p.T = desc->T; p.Hq = desc->Hq; p.Hkv = desc->Hkv; p.d = desc->dk;
+  p.gate_scale = desc->gate_scale; p.eps = desc->eps; p.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
+  p.seg_len = plan.seg_len; p.nseg = plan.nseg;
+  return hip_status(launch_gla_backward(p, static_cast<hipStream_t>(stream)));
 }
 
 int lawcat_gate_project(const lawcat_desc* desc, int d_model, int rank, const void* x, const void* w1, const void* w2,

@@ -25,6 +25,25 @@ hipError_t launch_conv1d(const ConvParams& p, hipStream_t stream);
 hipError_t launch_conv_tail(const ConvParams& p, hipStream_t stream);
 // Conv followed by the shared linear layer with nonlinearity (section 4.1): y = phi(conv(x) Wf), Wf [H / group, d, d]
 // in the storage type; head h uses matrix h / group.  p.tail_out is not written (see launch_conv_tail).
+// Adjoint of the normalized gated linear attention: gradients with respect to q-dot, k-dot, v, the gate logits and
+// the start state, given dO and the forward's den.
+struct GlaBackwardParams {
+  const void *q, *k, *v, *g;   // as lawcat_gla_prefill took them
+  const void* dO;              // [B,T,Hq,d] storage type
+  const float* den;            // [B,T,Hq]
+  const float *S0, *z0;        // nullable
+  void *dq, *dk, *dv, *dg;     // storage type, shapes of q, k, v, g
+  float *dS0, *dz0;            // nullable
+  void* workspace;
+  int B, T, Hq, Hkv, d;
+  float gate_scale, eps;
+  int bf16;
+  int seg_len, nseg;           // segments of the sequence (one workgroup each per sweep)
+};
+bool gla_backward_supports(int d, int group);
+size_t gla_backward_workspace_bytes(int B, int T, int Hq, int Hkv, int d, int seg_len, int nseg);
+hipError_t launch_gla_backward(const GlaBackwardParams& p, hipStream_t stream);
+
 // gate logits from the layer input: g = (x w1^T) w2^T + bias (two consecutive low-rank linear layers)
 struct GateProjectParams {
   const void *x, *w1, *w2, *bias;  // [B,T,dm], [rank,dm], [N,rank], [N] or null; storage type

@@ -246,6 +246,26 @@ def test_gate_project_argument_checks():
     assert call(desc=lawcat.make_desc(1, 0, 32, 8, 64)) == -2
 
 
+def test_gla_backward_argument_checks():
+    L = lawcat.lib()
+    d = lawcat.make_desc(1, 4096, 32, 8, 64)
+    need = lawcat.workspace_bytes(d, lawcat.CALL_GLA_BACKWARD)
+    # dnum, dden and the gate term per token in fp32, two sets of segment states, the gate totals
+    plan_slots = (need - 256) // 4 - 4096 * (32 * 64 + 32 + 8 * 64)
+    assert need > 0 and plan_slots > 0 and plan_slots % (8 * (2 * (64 * 64 + 128) + 64)) == 0
+
+    def call(desc=d, q=A, den=A, dO=A, dq=A, dS0=None, ws=A, nbytes=need):
+        return L.lawcat_gla_backward(ctypes.byref(desc), q, A, A, A, den, dO, None, None, dq, A, A, A, dS0, None,
+                                     ws, nbytes, None)
+
+    assert call(q=None) == -1 and call(den=None) == -1 and call(dO=None) == -1 and call(dq=None) == -1
+    assert call(dS0=ctypes.c_void_p(0x1004)) == -5
+    assert call(ws=None) == -4 and call(nbytes=need - 1) == -4
+    assert call(desc=lawcat.make_desc(1, 0, 32, 8, 64)) == -2
+    assert call(desc=lawcat.make_desc(1, 4096, 64, 2, 64)) == -3      # 32 query heads per kv head: staging too large
+    assert lawcat.workspace_bytes(lawcat.make_desc(1, 4096, 32, 8, 128), lawcat.CALL_GLA_BACKWARD) > need
+
+
 def test_packed_batch_plan_fits_the_chip_in_one_round():
     """The one-launch plan of a packed batch: the workspace grows with the longest sequence only through its segment
     count, many short sequences get one segment each, and lengthening the segments keeps the workgroups within

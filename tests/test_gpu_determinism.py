@@ -90,3 +90,36 @@ def test_matrix_core_side_kernels_are_bit_identical(d):
             continue
         for name in cur:
             assert torch.equal(_bits(cur[name]), _bits(first[name])), f"d={d}: {name} of call {it} differs from call 0"
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_backward_is_bit_identical(d):
+    """The backward adds the rows of dv through shuffles and LDS in a fixed order and carries segment states
+    through an ordered scan: no atomics, so repeated calls agree bit for bit (several segments per head)."""
+    wl = Workload("det_bwd", B=2, T=3000, Hq=8, Hkv=2, d=d)
+    dt = torch.bfloat16
+    x = make_inputs(wl, seed=9, state=True)
+    desc = H.desc_for(wl)
+    q, k = (torch.nn.functional.elu(H.dev(x[n], dt).float()).add(1).to(dt) for n in ("Q", "K"))
+    v, g, S0, z0 = H.dev(x["V"], dt), H.dev(x["G"], dt), H.dev(x["S0"]), H.dev(x["z0"])
+    o = torch.empty_like(q)
+    den = torch.empty(wl.B, wl.T, wl.Hq, device="cuda")
+    ws = lawcat.alloc_workspace(desc, lawcat.CALL_GLA_PREFILL)
+    lawcat.gla_prefill(desc, q, k, v, g, S0, z0, o, den, torch.empty_like(S0), torch.empty_like(z0), ws)
+    dO = torch.randn(o.shape, device="cuda", generator=torch.Generator("cuda").manual_seed(3)).to(dt)
+    wb = lawcat.alloc_workspace(desc, lawcat.CALL_GLA_BACKWARD)
+    first = None
+    for it in range(RUNS):
+        cur = {"dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v), "dg": torch.empty_like(g),
+               "dS0": torch.empty_like(S0), "dz0": torch.empty_like(z0)}
+        wb.fill_(0xFF)     # NaN patterns: nothing is read before it is written
+        lawcat.gla_backward(desc, q, k, v, g, den, dO, S0, z0, cur["dq"], cur["dk"], cur["dv"], cur["dg"], cur["dS0"],
+                            cur["dz0"], wb)
+        torch.cuda.synchronize()
+        for name, t in cur.items():
+            assert torch.isfinite(t.float()).all(), f"d={d}: {name} of call {it} is not finite"
+        if first is None:
+            first = cur
+            continue
+        for name in cur:
+            assert torch.equal(_bits(cur[name]), _bits(first[name])), f"d={d}: {name} of call {it} differs from call 0"
