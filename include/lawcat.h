@@ -154,8 +154,8 @@ LAWCAT_API int lawcat_gla_prefill(const lawcat_desc* desc, const void* q, const 
  *   output O itself is not needed);  dO [B,T,Hq,dv];  dq, dk, dv, dgate_logits: shapes and type of q, k, v,
  *   gate_logits;  dS0 [B,Hkv,dk,dv], dz0 [B,Hkv,dk]: nullable.  Workspace: LAWCAT_CALL_GLA_BACKWARD.
  * fp32 vector arithmetic throughout (both storage types), parallel over (batch, kv head) and segments of the
- * sequence; a first version, several times the forward's time.  More than 16 query heads per kv head (fewer at
- * head dim 128, where the staging of a token must fit LDS) is LAWCAT_E_UNSUPPORTED.
+ * sequence; a first version, several times the forward's time.  Query heads per kv head x head dim above 2048
+ * (the staging of one token's query heads) is LAWCAT_E_UNSUPPORTED.
  */
 LAWCAT_API int lawcat_gla_backward(const lawcat_desc* desc, const void* q, const void* k, const void* v,
                         const void* gate_logits, const float* den, const void* dO,

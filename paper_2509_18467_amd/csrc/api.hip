@@ -99,10 +99,8 @@ size_t workspace_bytes_checked(const lawcat_desc* d, int which) {
       return align_up(rows * d->Hq * d->dk * elem_bytes(d), 256) + align_up(rows * d->Hkv * d->dk * elem_bytes(d), 256) +
              align_up(inner, 256);
     }
-    case LAWCAT_CALL_GLA_BACKWARD: {
-      const ChunkPlan plan = plan_for(d);
-      return gla_backward_workspace_bytes(d->B, d->T, d->Hq, d->Hkv, d->dk, plan.seg_len, plan.nseg);
-    }
+    case LAWCAT_CALL_GLA_BACKWARD:
+      return gla_backward_workspace_bytes(d->B, d->T, d->Hq, d->Hkv, d->dk);
     default:
       return 0;
   }
@@ -196,13 +194,11 @@ int lawcat_gla_backward(const lawcat_desc* desc, const void* q, const void* k, c
     return LAWCAT_E_ALIGN;
   const size_t need = workspace_bytes_checked(desc, LAWCAT_CALL_GLA_BACKWARD);
   if (workspace == nullptr || workspace_bytes < need) return LAWCAT_E_WORKSPACE;
-  const ChunkPlan plan = plan_for(desc);
   GlaBackwardParams p{};
   p.q = q; p.k = k; p.v = v; p.g = gate_logits; p.den = den; p.dO = dO; p.S0 = S0; p.z0 = z0;
   p.dq = dq; p.dk = dk; p.dv = dv; p.dg = dgate_logits; p.dS0 = dS0; p.dz0 = dz0; p.workspace = workspace;
   p.B = desc->B; p.T = desc->T; p.Hq = desc->Hq; p.Hkv = desc->Hkv; p.d = desc->dk;
   p.gate_scale = desc->gate_scale; p.eps = desc->eps; p.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
-  p.seg_len = plan.seg_len; p.nseg = plan.nseg;
   return hip_status(launch_gla_backward(p, static_cast<hipStream_t>(stream)));
 }
 

@@ -16,7 +16,8 @@
 // state in registers: thread = one key channel (row) x a run of value columns, so products that contract the
 // value dimension (dq, dk) reduce inside a few adjacent lanes; dv contracts the key dimension and is reduced
 // through shuffles and LDS in a fixed order (no atomics: repeated calls agree bit for bit).  Tokens are staged
-// through LDS in blocks.  A first version: correct and segment-parallel, several times the forward's time.
+// through LDS in blocks of up to 8, the next block's loads in flight while the current one is worked on.
+// A first version: correct and segment-parallel, several times the forward's time.
 #include <mutex>
 
 #include "kernels.h"
@@ -39,57 +40,101 @@ struct BwdArgs {
   const float *S0, *z0;
   void *dq, *dk, *dv, *dg;
   float *dS0, *dz0;
-  float* dnum;       // [B,T,Hq,D]
   float* dden;       // [B,T,Hq]
   float* slots_f;    // [heads][nseg][D*D + 2D]: forward contributions, then start states
   float* slots_r;    // the same for Gr, segments in reverse order
   float* gate_local; // [B,T,Hkv,D]: sum_h q (.) dq, then the suffix sum of the gate term within the segment
   float* gate_tot;   // [heads][nseg][D]: the segment's total, then the sum over all later segments
-  int B, T, Hq, Hkv, group, seg_len, nseg, tb;
+  int B, T, Hq, Hkv, group, seg_len, nseg;
   float gate_scale, eps;
 };
 
-// ---- dnum = dO / den
-template <typename T, int D>
-__global__ void __launch_bounds__(256) bwd_prepare_kernel(const T* __restrict__ dO, const float* __restrict__ den,
-                                                         float* __restrict__ dnum, long long total) {
-  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i < total) dnum[i] = ldf(dO + i) / den[i / D];
-}
-
 enum { kFwdContrib = 0, kFwdOut = 1, kRevContrib = 2, kRevOut = 3 };
 
-// grid (nseg, B * Hkv), 256 threads, dynamic LDS.
-template <typename T, int D, int MODE>
+constexpr int pad4(int n) { return (n + 3) & ~3; }
+
+// LDS floats of a sweep that stages TB tokens: alpha | k, v | q, dnum per query head, den or dden per head |
+// forward outputs: S dnum^T per head, z, dden | reverse outputs: sum_h q (.) dq, dk, gate suffix, dv of the 4 waves
+template <int D, int MODE>
+constexpr int lds_floats(int TB, int group) {
+  int n = TB * D;
+  if (MODE != kRevContrib) n += 2 * TB * D;
+  if (MODE != kFwdContrib) n += 2 * TB * group * D + pad4(TB * group);
+  if (MODE == kFwdOut) n += TB * group * D + 2 * TB * D;
+  if (MODE == kRevOut) n += 3 * TB * D + 4 * TB * D;
+  return n;
+}
+
+// value of the lane whose index differs in bit 0 / bit 1 (inside a group of four lanes: no LDS traffic)
+__device__ inline float lane_xor1(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+}
+__device__ inline float lane_xor2(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
+}
+// sum over the TPR adjacent lanes that share a state row
+template <int TPR>
+__device__ inline float row_sum(float x) {
+  x += lane_xor1(x);
+  if (TPR == 4) x += lane_xor2(x);
+  return x;
+}
+
+// Sum over the rows of a wave by recursive halving: with lane stride M a lane hands the half of its columns that
+// its partner keeps and adds the partner's half of its own; after the last step a lane holds CNT columns, summed
+// over all the wave's rows, starting at column (row within the wave) * CNT of its run.  Fixed order.
+template <int CNT, int M, int MSTOP>
+__device__ inline void halve_rows(float* pv, int lane) {
+  if constexpr (M >= MSTOP) {
+    constexpr int H = CNT / 2;
+    const bool upper = (lane & M) != 0;
+#pragma unroll
+    for (int j = 0; j < H; ++j) {
+      const float send = upper ? pv[j] : pv[j + H];
+      const float keep = upper ? pv[j + H] : pv[j];
+      pv[j] = keep + __shfl_xor(send, M, 64);
+    }
+    halve_rows<H, M / 2, MSTOP>(pv, lane);
+  }
+}
+
+// grid (nseg, B * Hkv), 256 threads, dynamic LDS.  GR = query heads per kv head (0: read from the arguments, and
+// one token per block); EI = ceil(group * D / 256) elements of a token's query heads per thread; 8 / EI tokens
+// are staged per block, fetched into registers while the block before is worked on.
+template <typename T, int D, int MODE, int GR>
 __global__ void __launch_bounds__(256) bwd_pass_kernel(const BwdArgs a) {
   constexpr int TPR = 256 / D;       // threads per state row
   constexpr int CPT = D / TPR;       // value columns per thread
+  constexpr int EI = GR ? (GR * D + 255) / 256 : 8;
+  constexpr int TB = 8 / EI;         // tokens per block
+  constexpr int UH = GR ? GR : 1;    // unroll of the loops over the query heads
+  constexpr int KV = (TB * D + 255) / 256;   // elements of k, v, gate per thread and block
+  constexpr int FIN = CPT / (64 / TPR);      // columns of dv a lane ends up with
   constexpr bool REV = MODE >= kRevContrib;
   constexpr bool OUT = MODE == kFwdOut || MODE == kRevOut;
   constexpr int kSlot = D * D + 2 * D;
-  extern __shared__ float sm[];
-  const int tid = threadIdx.x;
+  extern __shared__ __align__(16) float sm[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = tid / TPR, j0 = (tid % TPR) * CPT;
   const int seg = blockIdx.x, bh = blockIdx.y;
   const int b = bh / a.Hkv, hk = bh % a.Hkv;
-  const int group = a.group, tb = a.tb;
+  const int group = GR ? GR : a.group, gD = group * D;
   const int s0 = seg * a.seg_len, s1 = min(a.T, s0 + a.seg_len);
-  // LDS: per staged token  alpha[D] k[D] v[D] | per head q[D] dn[D] dq[D] | dd[group] ; then the output staging
-  float* s_al = sm;
-  float* s_k = s_al + tb * D;
-  float* s_v = s_k + tb * D;
-  float* s_q = s_v + tb * D;                 // [tb][group][D]
-  float* s_dn = s_q + tb * group * D;        // [tb][group][D]
-  float* s_dq = s_dn + tb * group * D;       // [tb][group][D]: dq out (forward) / dq in (reverse)
-  float* s_dd = s_dq + tb * group * D;       // [tb][group]
-  float* s_dk = s_dd + tb * group;           // [tb][D]
-  float* s_gl = s_dk + tb * D;               // [tb][D]
-  float* s_dv = s_gl + tb * D;               // [tb][4 waves][D]
+  // LDS, in the order of lds_floats()
+  float* w = sm;
+  float* s_al = w; w += TB * D;
+  float *s_k = nullptr, *s_v = nullptr, *s_q = nullptr, *s_dn = nullptr, *s_dd = nullptr, *s_dq = nullptr;
+  float *s_dk = nullptr, *s_gl = nullptr, *s_dv = nullptr;
+  if (MODE != kRevContrib) { s_k = w; w += TB * D; s_v = w; w += TB * D; }
+  if (MODE != kFwdContrib) { s_q = w; w += TB * gD; s_dn = w; w += TB * gD; s_dd = w; w += pad4(TB * group); }
+  if (MODE == kFwdOut) { s_dq = w; w += TB * gD; s_dk = w; w += TB * D; s_gl = w; }   // S dnum^T | z_t | dden
+  if (MODE == kRevOut) { s_dq = w; w += TB * D; s_dk = w; w += TB * D; s_gl = w; w += TB * D; s_dv = w; }
 
   const T* q = static_cast<const T*>(a.q);
   const T* k = static_cast<const T*>(a.k);
   const T* v = static_cast<const T*>(a.v);
   const T* g = static_cast<const T*>(a.g);
+  const T* dO = static_cast<const T*>(a.dO);
 
   // ---- state of this thread: row c, columns j0 .. j0 + CPT - 1, and the normalizer column
   float X[CPT], xz = 0.f, decay = 1.f, gsum = 0.f;
@@ -112,103 +157,165 @@ __global__ void __launch_bounds__(256) bwd_pass_kernel(const BwdArgs a) {
     if (zsrc) xz = zsrc[c];
   }
 
-  const int len = s1 - s0;
-  const int nblk = (len + tb - 1) / tb;
-  for (int bi = 0; bi < nblk; ++bi) {
-    const int blk = REV ? nblk - 1 - bi : bi;
-    const int t_lo = s0 + blk * tb;
-    const int n = min(tb, s1 - t_lo);
-    // ---- stage the block's tokens
-    for (int idx = tid; idx < n * D; idx += 256) {
-      const int tl = idx / D, cc = idx % D;
-      const size_t row = ((size_t)b * a.T + t_lo + tl) * a.Hkv + hk;
-      const float gl = ldf(g + row * D + cc);
-      s_al[idx] = a.gate_scale == 1.0f ? 1.f / (1.f + expf(-gl)) : expf(a.gate_scale * log_sigmoid(gl));
-      s_k[idx] = ldf(k + row * D + cc);
-      s_v[idx] = ldf(v + row * D + cc);
+  // ---- a block's inputs, first into registers (fetch), a block later into LDS (stash)
+  float pg[KV], pk[KV], pv_[KV], pqd[KV], pq[TB * EI], pdo[TB * EI], pden[TB * EI], pdd = 0.f;
+  const int ddt = tid / group, ddh = tid - ddt * group;      // (token, head) of this thread's den / dden element
+  auto fetch = [&](int blk) {
+    const int t_lo = s0 + blk * TB;
+    const int n = min(TB, s1 - t_lo);
+#pragma unroll
+    for (int i = 0; i < KV; ++i) {
+      const int idx = i * 256 + tid;
+      if (idx < n * D) {
+        const size_t at = (((size_t)b * a.T + t_lo + idx / D) * a.Hkv + hk) * D + idx % D;
+        pg[i] = ldf(g + at);
+        if (MODE != kRevContrib) {
+          pk[i] = ldf(k + at);
+          pv_[i] = ldf(v + at);
+        }
+        if (MODE == kRevOut) pqd[i] = a.gate_local[at];
+      }
     }
     if (MODE != kFwdContrib) {
-      for (int idx = tid; idx < n * group * D; idx += 256) {
-        const int tl = idx / (group * D), hh = (idx / D) % group, cc = idx % D;
-        const size_t row = ((size_t)b * a.T + t_lo + tl) * a.Hq + hk * group + hh;
-        s_dn[idx] = a.dnum[row * D + cc];
-        s_q[idx] = ldf(q + row * D + cc);
-      }
-      if (MODE == kRevOut) {
-        // sum_h q (.) dq as the forward sweep left it, in fp32: against k (.) dk it nearly cancels, and dq rounded
-        // to the storage type would not do
-        for (int idx = tid; idx < n * D; idx += 256) {
-          const size_t row = ((size_t)b * a.T + t_lo + idx / D) * a.Hkv + hk;
-          s_dq[idx] = a.gate_local[row * D + idx % D];
+#pragma unroll
+      for (int tl = 0; tl < TB; ++tl) {
+        if (tl < n) {
+          const size_t row0 = ((size_t)b * a.T + t_lo + tl) * a.Hq + (size_t)hk * group;
+#pragma unroll
+          for (int e = 0; e < EI; ++e) {
+            const int el = e * 256 + tid;
+            if (el < gD) {
+              pq[tl * EI + e] = ldf(q + row0 * D + el);
+              pdo[tl * EI + e] = ldf(dO + row0 * D + el);
+              pden[tl * EI + e] = a.den[row0 + el / D];
+            }
+          }
         }
       }
-      for (int idx = tid; idx < n * group; idx += 256) {
-        const size_t row = ((size_t)b * a.T + t_lo + idx / group) * a.Hq + hk * group + idx % group;
-        s_dd[idx] = REV ? a.dden[row] : a.den[row];   // the forward sweep forms dden itself, from den
+      if (tid < n * group) {
+        const size_t row = ((size_t)b * a.T + t_lo + ddt) * a.Hq + hk * group + ddh;
+        pdd = REV ? a.dden[row] : a.den[row];   // the forward sweep forms dden itself, from den
       }
     }
+  };
+  auto stash = [&](int n) {
+#pragma unroll
+    for (int i = 0; i < KV; ++i) {
+      const int idx = i * 256 + tid;
+      if (idx < n * D) {
+        s_al[idx] = a.gate_scale == 1.0f ? 1.f / (1.f + expf(-pg[i])) : expf(a.gate_scale * log_sigmoid(pg[i]));
+        if (MODE != kRevContrib) {
+          s_k[idx] = pk[i];
+          s_v[idx] = pv_[i];
+        }
+        // sum_h q (.) dq as the forward sweep left it, in fp32: against k (.) dk it nearly cancels, and dq rounded
+        // to the storage type would not do
+        if (MODE == kRevOut) s_dq[idx] = pqd[i];
+      }
+    }
+    if (MODE != kFwdContrib) {
+#pragma unroll
+      for (int tl = 0; tl < TB; ++tl) {
+        if (tl < n) {
+#pragma unroll
+          for (int e = 0; e < EI; ++e) {
+            const int el = e * 256 + tid;
+            if (el < gD) {
+              s_q[tl * gD + el] = pq[tl * EI + e];
+              s_dn[tl * gD + el] = pdo[tl * EI + e] / pden[tl * EI + e];     // dnum = dO / den
+            }
+          }
+        }
+      }
+      if (tid < n * group) s_dd[tid] = pdd;
+    }
+  };
+
+  const int len = s1 - s0;
+  const int nblk = (len + TB - 1) / TB;
+  if (nblk > 0) fetch(REV ? nblk - 1 : 0);
+  for (int bi = 0; bi < nblk; ++bi) {
+    const int blk = REV ? nblk - 1 - bi : bi;
+    const int t_lo = s0 + blk * TB;
+    const int n = min(TB, s1 - t_lo);
+    stash(n);
     __syncthreads();
+    if (bi + 1 < nblk) fetch(REV ? blk - 1 : blk + 1);
     // ---- the block's tokens, one after the other
     for (int ti = 0; ti < n; ++ti) {
       const int tl = REV ? n - 1 - ti : ti;
-      const float al = s_al[tl * D + c], kk = s_k[tl * D + c];
+      const float al = s_al[tl * D + c];
       if (!REV) {
         // S^_t = alpha_t (.) S^_{t-1} + k_t^T v^_t
+        const float kk = s_k[tl * D + c];
+        const float4* v4 = reinterpret_cast<const float4*>(s_v + tl * D + j0);
         xz = fmaf(al, xz, kk);
 #pragma unroll
-        for (int j = 0; j < CPT; ++j) X[j] = fmaf(al, X[j], kk * s_v[tl * D + j0 + j]);
+        for (int j = 0; j < CPT / 4; ++j) {
+          const float4 vv = v4[j];
+          X[4 * j + 0] = fmaf(al, X[4 * j + 0], kk * vv.x);
+          X[4 * j + 1] = fmaf(al, X[4 * j + 1], kk * vv.y);
+          X[4 * j + 2] = fmaf(al, X[4 * j + 2], kk * vv.z);
+          X[4 * j + 3] = fmaf(al, X[4 * j + 3], kk * vv.w);
+        }
         decay *= al;
         if (MODE == kFwdOut) {
-          // u[c] = S_t[c, :] . dnum;  dden = -(q . u) / den needs all rows: this wave's share goes to LDS, the
-          // four are added and dq = u + z dden is formed after the block
-          if (tid % TPR == 0) s_dk[tl * D + c] = xz;           // z_t of this row (s_dk is free in this sweep)
+          // u[c] = S_t[c, :] . dnum;  dden = -(q . u) / den needs all rows: formed after the block, and then
+          // dq = u + z dden
+          if (tid % TPR == 0) s_dk[tl * D + c] = xz;           // z_t of this row
+#pragma unroll UH
           for (int hh = 0; hh < group; ++hh) {
-            const float* dn = s_dn + (tl * group + hh) * D + j0;
+            const float4* dn = reinterpret_cast<const float4*>(s_dn + (tl * group + hh) * D + j0);
             float acc = 0.f;
 #pragma unroll
-            for (int j = 0; j < CPT; ++j) acc = fmaf(X[j], dn[j], acc);
-#pragma unroll
-            for (int m = TPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, TPR);
-            float part = 0.f;
-            if (tid % TPR == 0) {
-              s_dq[(tl * group + hh) * D + c] = acc;
-              part = s_q[(tl * group + hh) * D + c] * acc;
+            for (int j = 0; j < CPT / 4; ++j) {
+              const float4 d4 = dn[j];
+              acc = fmaf(X[4 * j + 0], d4.x, acc);
+              acc = fmaf(X[4 * j + 1], d4.y, acc);
+              acc = fmaf(X[4 * j + 2], d4.z, acc);
+              acc = fmaf(X[4 * j + 3], d4.w, acc);
             }
-#pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) part += __shfl_xor(part, m, 64);
-            if ((tid & 63) == 0) s_gl[(tl * group + hh) * 4 + (tid >> 6)] = part;   // s_gl is free in this sweep
+            acc = row_sum<TPR>(acc);
+            if (tid % TPR == 0) s_dq[(tl * group + hh) * D + c] = acc;
           }
         }
       } else {
         // Gr_t = (what flows in from token t + 1) + sum_h q_t^T d^_t
+#pragma unroll UH
         for (int hh = 0; hh < group; ++hh) {
           const float qc = s_q[(tl * group + hh) * D + c];
-          const float* dn = s_dn + (tl * group + hh) * D + j0;
+          const float4* dn = reinterpret_cast<const float4*>(s_dn + (tl * group + hh) * D + j0);
           xz = fmaf(qc, s_dd[tl * group + hh], xz);
 #pragma unroll
-          for (int j = 0; j < CPT; ++j) X[j] = fmaf(qc, dn[j], X[j]);
+          for (int j = 0; j < CPT / 4; ++j) {
+            const float4 d4 = dn[j];
+            X[4 * j + 0] = fmaf(qc, d4.x, X[4 * j + 0]);
+            X[4 * j + 1] = fmaf(qc, d4.y, X[4 * j + 1]);
+            X[4 * j + 2] = fmaf(qc, d4.z, X[4 * j + 2]);
+            X[4 * j + 3] = fmaf(qc, d4.w, X[4 * j + 3]);
+          }
         }
         if (MODE == kRevOut) {
           // dk_t[c] = Gr_t[c, :] . v^_t
+          const float kk = s_k[tl * D + c];
+          const float4* v4 = reinterpret_cast<const float4*>(s_v + tl * D + j0);
           float acc = (tid % TPR == 0) ? xz : 0.f;
           float pv[CPT];
 #pragma unroll
-          for (int j = 0; j < CPT; ++j) {
-            acc = fmaf(X[j], s_v[tl * D + j0 + j], acc);
-            pv[j] = kk * X[j];               // this row's share of dv_t
+          for (int j = 0; j < CPT / 4; ++j) {
+            const float4 vv = v4[j];
+            acc = fmaf(X[4 * j + 0], vv.x, acc);
+            acc = fmaf(X[4 * j + 1], vv.y, acc);
+            acc = fmaf(X[4 * j + 2], vv.z, acc);
+            acc = fmaf(X[4 * j + 3], vv.w, acc);
           }
 #pragma unroll
-          for (int m = TPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, TPR);
-          // dv_t[col] = sum over the rows: first the rows of this wave (lanes with the same column run) ...
+          for (int j = 0; j < CPT; ++j) pv[j] = kk * X[j];               // this row's share of dv_t
+          acc = row_sum<TPR>(acc);
+          // dv_t[col] = sum over the rows: first the rows of this wave, then the four waves (below)
+          halve_rows<CPT, 32, TPR>(pv, lane);
 #pragma unroll
-          for (int m = TPR; m < 64; m <<= 1) {
-#pragma unroll
-            for (int j = 0; j < CPT; ++j) pv[j] += __shfl_xor(pv[j], m, 64);
-          }
-          if ((tid & 63) < TPR) {
-#pragma unroll
-            for (int j = 0; j < CPT; ++j) s_dv[(tl * 4 + (tid >> 6)) * D + j0 + j] = pv[j];   // ... then the four waves, below
-          }
+          for (int f = 0; f < FIN; ++f) s_dv[(tl * 4 + wave) * D + j0 + (lane / TPR) * FIN + f] = pv[f];
           if (tid % TPR == 0) {
             s_dk[tl * D + c] = acc;
             // the gate term of this token and everything after it in the segment
@@ -226,15 +333,33 @@ __global__ void __launch_bounds__(256) bwd_pass_kernel(const BwdArgs a) {
     __syncthreads();
     // ---- the block's outputs, whole rows at a time
     if (MODE == kFwdOut) {
+      // dden of every (token, head) of the block (at most 32 pairs): eight threads per pair, each over every
+      // eighth key channel (rotated by the pair, so that the pairs of a wave read different banks)
+      {
+        const int p = tid >> 3, r = tid & 7;
+        float part = 0.f;
+        if (p < n * group) {
+#pragma unroll
+          for (int i = 0; i < D / 8; ++i) {
+            const int ch = (r + 8 * i + 8 * p) & (D - 1);
+            part = fmaf(s_q[p * D + ch], s_dq[p * D + ch], part);
+          }
+        }
+        part += lane_xor1(part);
+        part += lane_xor2(part);
+        part += __shfl_xor(part, 4, 64);
+        if (r == 0 && p < n * group) s_gl[p] = -part / s_dd[p];
+      }
+      __syncthreads();
       T* dq = static_cast<T*>(a.dq);
       for (int idx = tid; idx < n * D; idx += 256) {
         const int tl = idx / D, cc = idx % D;
         const size_t tok = (size_t)b * a.T + t_lo + tl;
         float qdq = 0.f;
+#pragma unroll UH
         for (int hh = 0; hh < group; ++hh) {
           const size_t row = tok * a.Hq + hk * group + hh;
-          const float* p = s_gl + (tl * group + hh) * 4;
-          const float dden = -((p[0] + p[1]) + (p[2] + p[3])) / s_dd[tl * group + hh];
+          const float dden = s_gl[tl * group + hh];
           const float dqv = fmaf(s_dk[tl * D + cc], dden, s_dq[(tl * group + hh) * D + cc]);
           stf(dq + row * D + cc, dqv);
           qdq = fmaf(s_q[(tl * group + hh) * D + cc], dqv, qdq);
@@ -345,26 +470,26 @@ __global__ void __launch_bounds__(256) bwd_gate_finish_kernel(const T* __restric
   stf(dg + i, (local[i] + later) * gate_scale * (1.f - sg));
 }
 
-template <typename T, int D>
-hipError_t launch_typed(const GlaBackwardParams& p, const BwdArgs& a, hipStream_t stream) {
+template <typename T, int D, int GR>
+hipError_t launch_sized(const GlaBackwardParams& p, const BwdArgs& a, hipStream_t stream) {
+  constexpr int TB = GR ? 8 / ((GR * D + 255) / 256) : 1;
   const int heads = p.B * p.Hkv;
-  const long long nd = (long long)p.B * p.T * p.Hq * D;
-  hipLaunchKernelGGL((bwd_prepare_kernel<T, D>), dim3((unsigned)((nd + 255) / 256)), dim3(256), 0, stream, (const T*)p.dO,
-                     p.den, a.dnum, nd);
-  const size_t lds = (size_t)a.tb * (3 * D + a.group * (3 * D + 1) + 2 * D + 4 * D) * sizeof(float);
   const dim3 grid(a.nseg, heads);
+  const auto bytes = [&](int floats) { return (size_t)floats * sizeof(float); };
   if (a.nseg > 1) {
-    hipLaunchKernelGGL((bwd_pass_kernel<T, D, kFwdContrib>), grid, dim3(256), lds, stream, a);
+    hipLaunchKernelGGL((bwd_pass_kernel<T, D, kFwdContrib, GR>), grid, dim3(256), bytes(lds_floats<D, kFwdContrib>(TB, a.group)),
+                       stream, a);
     hipLaunchKernelGGL((bwd_scan_kernel<D>), dim3((D * D + D + 255) / 256, heads), dim3(256), 0, stream, a.slots_f, p.S0,
                        p.z0, a.nseg);
   }
-  hipLaunchKernelGGL((bwd_pass_kernel<T, D, kFwdOut>), grid, dim3(256), lds, stream, a);
+  hipLaunchKernelGGL((bwd_pass_kernel<T, D, kFwdOut, GR>), grid, dim3(256), bytes(lds_floats<D, kFwdOut>(TB, a.group)), stream, a);
   if (a.nseg > 1) {
-    hipLaunchKernelGGL((bwd_pass_kernel<T, D, kRevContrib>), grid, dim3(256), lds, stream, a);
+    hipLaunchKernelGGL((bwd_pass_kernel<T, D, kRevContrib, GR>), grid, dim3(256), bytes(lds_floats<D, kRevContrib>(TB, a.group)),
+                       stream, a);
     hipLaunchKernelGGL((bwd_scan_kernel<D>), dim3((D * D + D + 255) / 256, heads), dim3(256), 0, stream, a.slots_r,
                        (const float*)nullptr, (const float*)nullptr, a.nseg);
   }
-  hipLaunchKernelGGL((bwd_pass_kernel<T, D, kRevOut>), grid, dim3(256), lds, stream, a);
+  hipLaunchKernelGGL((bwd_pass_kernel<T, D, kRevOut, GR>), grid, dim3(256), bytes(lds_floats<D, kRevOut>(TB, a.group)), stream, a);
   if (a.nseg > 1) hipLaunchKernelGGL((bwd_gate_suffix_kernel<D>), dim3(heads), dim3(D), 0, stream, a.gate_tot, a.nseg);
   const long long total = (long long)p.B * p.T * p.Hkv * D;
   hipLaunchKernelGGL((bwd_gate_finish_kernel<T, D>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
@@ -372,22 +497,41 @@ hipError_t launch_typed(const GlaBackwardParams& p, const BwdArgs& a, hipStream_
   return hipGetLastError();
 }
 
-}  // namespace
-
-// Tokens staged per block: as many as keep the staging under 48 KB of LDS.
-static int backward_block_tokens(int d, int group) {
-  const size_t per_token = (size_t)(3 * d + group * (3 * d + 1) + 2 * d + 4 * d) * sizeof(float);
-  int tb = (int)(48 * 1024 / per_token);
-  return tb > 16 ? 16 : tb;
+template <typename T, int D>
+hipError_t launch_typed(const GlaBackwardParams& p, const BwdArgs& a, hipStream_t stream) {
+  switch (a.group) {
+    case 1: return launch_sized<T, D, 1>(p, a, stream);
+    case 2: return launch_sized<T, D, 2>(p, a, stream);
+    case 4: return launch_sized<T, D, 4>(p, a, stream);
+    case 8: return launch_sized<T, D, 8>(p, a, stream);
+    default: return launch_sized<T, D, 0>(p, a, stream);     // any other group: one token per block
+  }
 }
 
-// (the forward sweep parks four partial sums per query head in a row of d floats)
-bool gla_backward_supports(int d, int group) { return backward_block_tokens(d, group) >= 1 && group * 4 <= d; }
+}  // namespace
 
-size_t gla_backward_workspace_bytes(int B, int T, int Hq, int Hkv, int d, int seg_len, int nseg) {
+// A token's query heads are staged by 256 threads in at most 8 rounds; dden of a block's (token, head) pairs must
+// fit one LDS row of d floats per token.
+bool gla_backward_supports(int d, int group) { return group * d <= 2048 && group <= d; }
+
+// Segments of the sequence: about four workgroups per compute unit over all (batch, kv head) pairs (what the
+// output sweeps' registers and LDS allow to be resident), segments a multiple of 64 tokens.
+void gla_backward_plan(int B, int T, int Hkv, int* seg_len, int* nseg) {
+  const long long heads = (long long)B * Hkv;
+  long long want = 1024 / heads;                 // segments per head
+  if (want < 1) want = 1;
+  long long len = (T + want - 1) / want;
+  len = (len + 63) / 64 * 64;
+  *seg_len = (int)len;
+  *nseg = (int)((T + len - 1) / len);
+}
+
+size_t gla_backward_workspace_bytes(int B, int T, int Hq, int Hkv, int d) {
+  int seg_len, nseg;
+  gla_backward_plan(B, T, Hkv, &seg_len, &nseg);
   const size_t rows = (size_t)B * T;
-  size_t n = rows * Hq * d + rows * Hq + rows * Hkv * d;           // dnum, dden, gate_local
-  n += 2 * (size_t)B * Hkv * nseg * (d * d + 2 * d);               // slots, both directions
+  size_t n = rows * Hq + rows * Hkv * d;                           // dden, gate term
+  n += 2 * (size_t)B * Hkv * nseg * (d * d + 2 * d);               // segment states, both directions
   n += (size_t)B * Hkv * nseg * d;                                 // gate totals
   return n * sizeof(float) + 256;
 }
@@ -396,17 +540,16 @@ hipError_t launch_gla_backward(const GlaBackwardParams& p, hipStream_t stream) {
   BwdArgs a{};
   a.q = p.q; a.k = p.k; a.v = p.v; a.g = p.g; a.dO = p.dO; a.den = p.den; a.S0 = p.S0; a.z0 = p.z0;
   a.dq = p.dq; a.dk = p.dk; a.dv = p.dv; a.dg = p.dg; a.dS0 = p.dS0; a.dz0 = p.dz0;
-  a.B = p.B; a.T = p.T; a.Hq = p.Hq; a.Hkv = p.Hkv; a.group = p.Hq / p.Hkv; a.seg_len = p.seg_len; a.nseg = p.nseg;
+  a.B = p.B; a.T = p.T; a.Hq = p.Hq; a.Hkv = p.Hkv; a.group = p.Hq / p.Hkv;
   a.gate_scale = p.gate_scale; a.eps = p.eps;
-  a.tb = backward_block_tokens(p.d, a.group);
-  if (a.tb < 1) return hipErrorInvalidValue;
+  gla_backward_plan(p.B, p.T, p.Hkv, &a.seg_len, &a.nseg);
+  if (!gla_backward_supports(p.d, a.group)) return hipErrorInvalidValue;
   const size_t rows = (size_t)p.B * p.T;
   float* w = static_cast<float*>(p.workspace);
-  a.dnum = w; w += rows * p.Hq * p.d;
   a.dden = w; w += rows * p.Hq;
   a.gate_local = w; w += rows * p.Hkv * p.d;
-  a.slots_f = w; w += (size_t)p.B * p.Hkv * p.nseg * (p.d * p.d + 2 * p.d);
-  a.slots_r = w; w += (size_t)p.B * p.Hkv * p.nseg * (p.d * p.d + 2 * p.d);
+  a.slots_f = w; w += (size_t)p.B * p.Hkv * a.nseg * (p.d * p.d + 2 * p.d);
+  a.slots_r = w; w += (size_t)p.B * p.Hkv * a.nseg * (p.d * p.d + 2 * p.d);
   a.gate_tot = w;
   if (p.bf16) return p.d == 64 ? launch_typed<bf16_t, 64>(p, a, stream) : launch_typed<bf16_t, 128>(p, a, stream);
   return p.d == 64 ? launch_typed<float, 64>(p, a, stream) : launch_typed<float, 128>(p, a, stream);

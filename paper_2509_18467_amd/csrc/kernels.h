@@ -38,10 +38,9 @@ struct GlaBackwardParams {
   int B, T, Hq, Hkv, d;
   float gate_scale, eps;
   int bf16;
-  int seg_len, nseg;           // segments of the sequence (one workgroup each per sweep)
 };
 bool gla_backward_supports(int d, int group);
-size_t gla_backward_workspace_bytes(int B, int T, int Hq, int Hkv, int d, int seg_len, int nseg);
+size_t gla_backward_workspace_bytes(int B, int T, int Hq, int Hkv, int d);
 hipError_t launch_gla_backward(const GlaBackwardParams& p, hipStream_t stream);
 
 // gate logits from the layer input: g = (x w1^T) w2^T + bias (two consecutive low-rank linear layers)

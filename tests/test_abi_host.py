@@ -250,9 +250,9 @@ def test_gla_backward_argument_checks():
     L = lawcat.lib()
     d = lawcat.make_desc(1, 4096, 32, 8, 64)
     need = lawcat.workspace_bytes(d, lawcat.CALL_GLA_BACKWARD)
-    # dnum, dden and the gate term per token in fp32, two sets of segment states, the gate totals
-    plan_slots = (need - 256) // 4 - 4096 * (32 * 64 + 32 + 8 * 64)
-    assert need > 0 and plan_slots > 0 and plan_slots % (8 * (2 * (64 * 64 + 128) + 64)) == 0
+    # dden and the gate term per token in fp32; two sets of segment states and the gate totals for 8 kv heads x 64
+    # segments of 64 tokens (about 1024 workgroups wanted)
+    assert need == 4 * (4096 * (32 + 8 * 64) + 8 * 64 * (2 * (64 * 64 + 128) + 64)) + 256
 
     def call(desc=d, q=A, den=A, dO=A, dq=A, dS0=None, ws=A, nbytes=need):
         return L.lawcat_gla_backward(ctypes.byref(desc), q, A, A, A, den, dO, None, None, dq, A, A, A, dS0, None,
@@ -262,7 +262,7 @@ def test_gla_backward_argument_checks():
     assert call(dS0=ctypes.c_void_p(0x1004)) == -5
     assert call(ws=None) == -4 and call(nbytes=need - 1) == -4
     assert call(desc=lawcat.make_desc(1, 0, 32, 8, 64)) == -2
-    assert call(desc=lawcat.make_desc(1, 4096, 64, 2, 64)) == -3      # 32 query heads per kv head: staging too large
+    assert call(desc=lawcat.make_desc(1, 4096, 64, 2, 128)) == -3     # 32 query heads of 128 per kv head: staging too large
     assert lawcat.workspace_bytes(lawcat.make_desc(1, 4096, 32, 8, 128), lawcat.CALL_GLA_BACKWARD) > need
 
 
