@@ -311,11 +311,26 @@ def run_side_ops(wl, steps=30):
     e1.record()
     torch.cuda.synchronize()
     bwd_ms = e0.elapsed_time(e1) / 5
+    # the conv's adjoint on the query side (6 B per element in bf16: x and dy read, dx written)
+    dw_ = torch.empty(wl.Hq, wl.d, wl.W, device="cuda")
+    dxq = torch.empty_like(dq_)
+    wsc = lawcat.alloc_workspace(desc, lawcat.CALL_CONV1D_BACKWARD)
+    for _ in range(2):
+        lawcat.conv1d_backward(desc, wl.Hq, xs[0], w, None, grads[0], dxq, dw_, None, wsc)
+    e0.record()
+    for _ in range(10):
+        lawcat.conv1d_backward(desc, wl.Hq, xs[0], w, None, grads[0], dxq, dw_, None, wsc)
+    e1.record()
+    torch.cuda.synchronize()
+    cbwd_ms = e0.elapsed_time(e1) / 10
+    cbwd_bytes = 3 * xs[0].numel() * xs[0].element_size()
     # multiply-adds on the d x (d + 1) state: both sweeps update it once per token and kv head and read it once per
     # query head (dq; q^T d^), plus dk and dv: 2 * (2 + 2 * group + 2) * d * d per token and kv head, sweeps run twice
     bwd_flops = 2.0 * wl.B * wl.T * wl.Hkv * wl.d * wl.d * (4 + 2 * wl.Hq // wl.Hkv)
     return {"gla_backward": {"ms": bwd_ms, "tokens_per_s": wl.B * wl.T / (bwd_ms * 1e-3),
                              "fp32_TFLOP/s_outputs_only": bwd_flops / (bwd_ms * 1e-3) / 1e12},
+            "conv1d_backward_q": {"ms": cbwd_ms, "GB/s": cbwd_bytes / (cbwd_ms * 1e-3) / 1e9,
+                                  "frac_of_hbm_peak": cbwd_bytes / (cbwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "gla_steps_block256": {"us_per_step": block_us},
             "gla_step_batch256": {"us_per_step": batch_us, "state_bytes_per_step": batch_bytes,
                                   "GB/s": batch_bytes / (batch_us * 1e-6) / 1e9,

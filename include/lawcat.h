@@ -71,7 +71,8 @@ enum {
   LAWCAT_CALL_GLA_STEP = 2,
   LAWCAT_CALL_LAYER_PREFILL = 3,
   LAWCAT_CALL_LAYER_PREFILL_FM = 4,
-  LAWCAT_CALL_GLA_BACKWARD = 5
+  LAWCAT_CALL_GLA_BACKWARD = 5,
+  LAWCAT_CALL_CONV1D_BACKWARD = 6 /* sized for Hq heads (the larger of the two convs) */
 };
 
 typedef struct lawcat_desc {
@@ -161,6 +162,22 @@ LAWCAT_API int lawcat_gla_backward(const lawcat_desc* desc, const void* q, const
                         const void* gate_logits, const float* den, const void* dO,
                         const float* S0, const float* z0, void* dq, void* dk, void* dv, void* dgate_logits,
                         float* dS0, float* dz0, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Adjoint of lawcat_conv1d_causal, pointwise feature map included (section 4.1; the distillation of section 5
+ * trains the conv weights): with u_t = sum_{delta<W} w[delta] x_{t-delta}, du_t = dy_t phi'(u_t) (phi' = 1 for the
+ * identity; for 1 + ELU: 1 where u > 0, exp(u) elsewhere; u is recomputed from x):
+ *   dx[b,s,h,c] = sum_{delta<W} w[h,c,delta] du[b,s+delta,h,c]        (tokens past the end contribute nothing)
+ *   dw[h,c,delta] = sum_{b,t} du[b,t,h,c] x[b,t-delta,h,c]            (fp32, whatever the storage type)
+ *   dhalo: the same sum as dx for the W-1 rows before the first token (nullable; written whether or not halo is given)
+ *   x, w, halo as lawcat_conv1d_causal took them; dy, dx [B,T,n_heads,d]; dhalo [B,W-1,n_heads,d]; dw [n_heads,d,W].
+ * Workspace: LAWCAT_CALL_CONV1D_BACKWARD (partial sums of dw per 64-token strip, added in a fixed order: repeated
+ * calls agree bit for bit).  A layer's backward is lawcat_gla_backward followed by this call on (Q, wq, dq) and on
+ * (K, wk, dk).
+ */
+LAWCAT_API int lawcat_conv1d_backward(const lawcat_desc* desc, int n_heads, const void* x, const void* w, const void* halo,
+                           const void* dy, void* dx, float* dw, void* dhalo, void* workspace,
+                           size_t workspace_bytes, void* stream);
 
 /*
  * Section 4.2, one recurrent (decode) step on one token per sequence; desc->T is ignored.

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liblawcat.so")
-SOURCES = ["api.hip", "conv1d.hip", "feature_map.hip", "gate_project.hip", "gla_backward.hip", "gla_recurrent.hip", "gla_chunk.hip", "gla_chunk_d64.hip", "gla_chunk_d128.hip"]
+SOURCES = ["api.hip", "conv1d.hip", "feature_map.hip", "gate_project.hip", "gla_backward.hip", "conv1d_backward.hip", "gla_recurrent.hip", "gla_chunk.hip", "gla_chunk_d64.hip", "gla_chunk_d128.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instructions are switched off on purpose: some of their forms have given wrong results on the test machines
 FLAGS = [

@@ -101,6 +101,8 @@ size_t workspace_bytes_checked(const lawcat_desc* d, int which) {
     }
     case LAWCAT_CALL_GLA_BACKWARD:
       return gla_backward_workspace_bytes(d->B, d->T, d->Hq, d->Hkv, d->dk);
+    case LAWCAT_CALL_CONV1D_BACKWARD:
+      return conv_backward_workspace_bytes(d->B, d->T, d->Hq, d->dk, d->conv_width);
     default:
       return 0;
   }
@@ -200,6 +202,27 @@ int lawcat_gla_backward(const lawcat_desc* desc, const void* q, const void* k, c
   p.B = desc->B; p.T = desc->T; p.Hq = desc->Hq; p.Hkv = desc->Hkv; p.d = desc->dk;
   p.gate_scale = desc->gate_scale; p.eps = desc->eps; p.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
   return hip_status(launch_gla_backward(p, static_cast<hipStream_t>(stream)));
+}
+
+int lawcat_conv1d_backward(const lawcat_desc* desc, int n_heads, const void* x, const void* w, const void* halo,
+                           const void* dy, void* dx, float* dw, void* dhalo, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+  int st = check_desc(desc, true);
+  if (st != LAWCAT_OK) return st;
+  if (n_heads <= 0) return LAWCAT_E_BAD_DESC;
+  if (!x || !w || !dy || !dx || !dw) return LAWCAT_E_NULL;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(halo) || !aligned16(dy) || !aligned16(dx) || !aligned16(dw) ||
+      !aligned16(dhalo) || !aligned16(workspace))
+    return LAWCAT_E_ALIGN;
+  if ((uint64_t)desc->B > 65535 || ((uint64_t)desc->T + 63) / 64 > 65535) return LAWCAT_E_UNSUPPORTED;   // grid limits
+  const size_t need = conv_backward_workspace_bytes(desc->B, desc->T, n_heads, desc->dk, desc->conv_width);
+  if (workspace == nullptr || workspace_bytes < need) return LAWCAT_E_WORKSPACE;
+  ConvBackwardParams p{};
+  p.x = x; p.w = w; p.halo = desc->conv_width > 1 ? halo : nullptr; p.dy = dy;
+  p.dx = dx; p.dw = dw; p.dhalo = desc->conv_width > 1 ? dhalo : nullptr; p.workspace = workspace;
+  p.B = desc->B; p.T = desc->T; p.H = n_heads; p.d = desc->dk; p.W = desc->conv_width;
+  p.phi = desc->feature_map; p.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
+  return hip_status(launch_conv_backward(p, static_cast<hipStream_t>(stream)));
 }
 
 int lawcat_gate_project(const lawcat_desc* desc, int d_model, int rank, const void* x, const void* w1, const void* w2,

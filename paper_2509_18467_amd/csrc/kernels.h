@@ -43,6 +43,18 @@ bool gla_backward_supports(int d, int group);
 size_t gla_backward_workspace_bytes(int B, int T, int Hq, int Hkv, int d);
 hipError_t launch_gla_backward(const GlaBackwardParams& p, hipStream_t stream);
 
+// Adjoint of launch_conv1d (conv + pointwise feature map): dx, dw (fp32, [H,d,W]) and dhalo from dy.
+struct ConvBackwardParams {
+  const void *x, *w, *halo, *dy;   // as the forward took them; halo nullable; dy [B,T,H,d]
+  void *dx, *dhalo;                // storage type; dhalo nullable [B,W-1,H,d]
+  float* dw;                       // [H,d,W]
+  void* workspace;                 // conv_backward_workspace_bytes()
+  int B, T, H, d, W;
+  int phi, bf16;
+};
+size_t conv_backward_workspace_bytes(int B, int T, int H, int d, int W);
+hipError_t launch_conv_backward(const ConvBackwardParams& p, hipStream_t stream);
+
 // gate logits from the layer input: g = (x w1^T) w2^T + bias (two consecutive low-rank linear layers)
 struct GateProjectParams {
   const void *x, *w1, *w2, *bias;  // [B,T,dm], [rank,dm], [N,rank], [N] or null; storage type

@@ -18,9 +18,10 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 PHI_IDENTITY, PHI_ELU1 = 0, 1
 CARRY_AUTO, CARRY_SEQUENTIAL, CARRY_TWO_LEVEL = 0, 1, 2
 CALL_CONV1D, CALL_GLA_PREFILL, CALL_GLA_STEP, CALL_LAYER_PREFILL, CALL_LAYER_PREFILL_FM, CALL_GLA_BACKWARD = 0, 1, 2, 3, 4, 5
+CALL_CONV1D_BACKWARD = 6
 
 EXPORTS = (
-    "lawcat_workspace_bytes", "lawcat_conv1d_causal", "lawcat_gate_project", "lawcat_gla_backward", "lawcat_gla_prefill", "lawcat_gla_step", "lawcat_gla_steps",
+    "lawcat_workspace_bytes", "lawcat_conv1d_backward", "lawcat_conv1d_causal", "lawcat_gate_project", "lawcat_gla_backward", "lawcat_gla_prefill", "lawcat_gla_step", "lawcat_gla_steps",
     "lawcat_conv1d_feature", "lawcat_layer_prefill", "lawcat_layer_prefill_varlen", "lawcat_varlen_workspace_bytes", "lawcat_layer_prefill_fm", "lawcat_layer_prefill_static",
     "lawcat_layer_prefill_timed", "lawcat_status_string", "lawcat_version",
 )
@@ -75,6 +76,8 @@ def lib() -> ctypes.CDLL:
         L.lawcat_version.restype = ci
         L.lawcat_gla_backward.argtypes = [dp] + [vp] * 15 + [sz, vp]
         L.lawcat_gla_backward.restype = ci
+        L.lawcat_conv1d_backward.argtypes = [dp, ci] + [vp] * 8 + [sz, vp]
+        L.lawcat_conv1d_backward.restype = ci
         L.lawcat_gate_project.argtypes = [dp, ci, ci] + [vp] * 6
         L.lawcat_gate_project.restype = ci
         L.lawcat_varlen_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_int32), ci]
@@ -162,6 +165,12 @@ def gla_backward(desc, q, k, v, gate_logits, den, dO, S0, z0, dq, dk, dv, dg, dS
     _check(lib().lawcat_gla_backward(ctypes.byref(desc), _p(q), _p(k), _p(v), _p(gate_logits), _p(den), _p(dO),
                                      _p(S0), _p(z0), _p(dq), _p(dk), _p(dv), _p(dg), _p(dS0), _p(dz0), _p(workspace),
                                      nbytes, _stream(stream)))
+
+
+def conv1d_backward(desc, n_heads, x, w, halo, dy, dx, dw, dhalo, workspace, stream=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().lawcat_conv1d_backward(ctypes.byref(desc), n_heads, _p(x), _p(w), _p(halo), _p(dy), _p(dx), _p(dw),
+                                        _p(dhalo), _p(workspace), nbytes, _stream(stream)))
 
 
 def gate_project(desc, d_model, rank, x, w1, w2, bias, gate_logits, stream=None):

@@ -266,6 +266,23 @@ def test_gla_backward_argument_checks():
     assert lawcat.workspace_bytes(lawcat.make_desc(1, 4096, 32, 8, 128), lawcat.CALL_GLA_BACKWARD) > need
 
 
+def test_conv1d_backward_argument_checks():
+    L = lawcat.lib()
+    d = lawcat.make_desc(2, 1000, 32, 8, 64)
+    need = lawcat.workspace_bytes(d, lawcat.CALL_CONV1D_BACKWARD)
+    assert need == 2 * 16 * 32 * 64 * 4 * 4          # (batch, 64-token strip) partial sums of dw [Hq, d, W] in fp32
+
+    def call(desc=d, heads=32, x=A, dy=A, dw=A, dhalo=None, ws=A, nbytes=need):
+        return L.lawcat_conv1d_backward(ctypes.byref(desc), heads, x, A, None, dy, A, dw, dhalo, ws, nbytes, None)
+
+    assert call(x=None) == -1 and call(dy=None) == -1 and call(dw=None) == -1
+    assert call(heads=0) == -2
+    assert call(dhalo=ctypes.c_void_p(0x1008)) == -5
+    assert call(ws=None) == -4 and call(nbytes=need - 1) == -4
+    assert call(heads=8, nbytes=need // 4 - 1) == -4             # the key conv needs a quarter of it
+    assert call(desc=lawcat.make_desc(2, 1000, 32, 8, 64, conv_width=5)) == -3
+
+
 def test_packed_batch_plan_fits_the_chip_in_one_round():
     """The one-launch plan of a packed batch: the workspace grows with the longest sequence only through its segment
     count, many short sequences get one segment each, and lengthening the segments keeps the workgroups within

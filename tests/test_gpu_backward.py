@@ -54,3 +54,87 @@ def test_gla_backward(oracle, name, T, gate_scale, start):
     for n in ("dq", "dk", "dv", "dg", "dS0", "dz0"):
         r = H.assert_close(got[n], ref[n], wl, f"gla_backward {n}", rnd if n in outs else 0)
         print(f"  {n}: error / bar {r:.3f}, max err / rms {H.rel_rms_err(got[n], ref[n]):.3e}", flush=True)
+
+
+def _abs_term_sum_dw(oracle, x, w, halo, dy, phi):
+    """sum over (b, t) of |du_t x_{t-delta}| per weight: the scale that the rounding error of an fp32 sum of
+    signed terms is measured against (tolerance only; the expected dw is the oracle's)."""
+    B, T, Hh, d = x.shape
+    W = w.shape[-1]
+    u = oracle.conv1d_causal(x, w, halo, 0)
+    du = np.abs(dy * (np.where(u > 0, 1.0, np.exp(np.minimum(u, 0.0))) if phi == 1 else 1.0))
+    prev = np.zeros((B, W - 1, Hh, d)) if halo is None else np.asarray(halo, dtype=np.float64)
+    full = np.abs(np.concatenate([prev, x], axis=1))
+    out = np.empty((Hh, d, W))
+    for dl in range(W):
+        out[:, :, dl] = (du * full[:, W - 1 - dl: W - 1 - dl + T]).sum(axis=(0, 1))
+    return out
+
+
+@pytest.mark.parametrize("name,B,T,W,phi,halo", [
+    ("tiny", 1, 77, 4, 1, True), ("tiny", 2, 130, 4, 0, False), ("tiny", 1, 5, 3, 1, True), ("tiny", 3, 64, 2, 1, False),
+    ("tiny", 1, 200, 1, 1, False), ("tiny", 1, 2, 4, 1, True),
+    ("llama1b_8k", 1, 1500, 4, 1, True), ("llama1b_8k", 2, 333, 4, 1, False), ("mistral7b_16k", 1, 700, 4, 1, True),
+    ("mistral7b_16k", 1, 129, 3, 0, True),
+])
+def test_conv1d_backward(oracle, name, B, T, W, phi, halo):
+    import dataclasses
+    wl = dataclasses.replace(WORKLOADS[name].with_T(T), B=B, W=W)
+    xin = make_inputs(wl, seed=21, halo=halo)
+    print("conv1d_backward", wl, "phi", phi, "halo", halo, flush=True)
+    x, w = xin["Q"], xin["wq"]
+    hl = xin.get("q_halo") if (halo and W > 1) else None
+    dy = _store(wl, np.random.default_rng(6).standard_normal(x.shape) * 0.5)
+    ref = oracle.conv1d_backward(x, w, dy, hl, phi)
+
+    dt = H.tdtype(wl)
+    desc = H.desc_for(wl, feature_map=phi)
+    dx = torch.empty(x.shape, dtype=dt, device="cuda")
+    dw = torch.empty(w.shape, dtype=torch.float32, device="cuda")
+    dh = torch.empty(B, W - 1, wl.Hq, wl.d, dtype=dt, device="cuda") if W > 1 else None
+    ws = lawcat.alloc_workspace(desc, lawcat.CALL_CONV1D_BACKWARD)
+    lawcat.conv1d_backward(desc, wl.Hq, H.dev(x, dt), H.dev(w, dt), H.dev(hl, dt), H.dev(dy, dt), dx, dw, dh, ws)
+    torch.cuda.synchronize()
+    rnd = 1 if wl.dtype == "bf16" else 0
+    r = H.assert_close(H.host(dx), ref["dx"], wl, "conv1d_backward dx", rnd)
+    print(f"  dx: error / bar {r:.3f}", flush=True)
+    if hl is not None:
+        r = H.assert_close(H.host(dh), ref["dhalo"], wl, "conv1d_backward dhalo", rnd)
+        print(f"  dhalo: error / bar {r:.3f}", flush=True)
+    # dw is an fp32 sum over all tokens of signed products: 64 fp32 ulps of the sum of their absolute values
+    scale = _abs_term_sum_dw(oracle, x, w, hl, dy, phi)
+    ratio = np.abs(H.host(dw) - ref["dw"]) / (2.0 ** -18 * scale + 1e-6)
+    print(f"  dw: error / bar {ratio.max():.3f}", flush=True)
+    assert ratio.max() <= 1.0, f"conv1d_backward dw: largest error is {ratio.max():.3f} of its bar"
+
+
+@pytest.mark.parametrize("name,T", [("llama1b_8k", 1300), ("mistral7b_16k", 500)])
+def test_layer_backward_as_a_chain_of_calls(oracle, name, T):
+    """lawcat_gla_backward, then lawcat_conv1d_backward on (Q, wq, dq) and (K, wk, dk), against the same chain of
+    the oracle's adjoints (pinned on the CPU against finite differences of the oracle's whole layer).  Each GPU
+    stage is fed the oracle's result of the stage before it, rounded to storage, as everywhere in this file."""
+    wl = WORKLOADS[name].with_T(T)
+    x = make_inputs(wl, seed=23, halo=True, state=True)
+    print("layer backward", wl, flush=True)
+    dt = H.tdtype(wl)
+    desc = H.desc_for(wl, feature_map=1)
+    q = _store(wl, oracle.conv1d_causal(x["Q"], x["wq"], x["q_halo"], 1))
+    k = _store(wl, oracle.conv1d_causal(x["K"], x["wk"], x["k_halo"], 1))
+    fwd = oracle.gla_prefill(q, k, x["V"], x["G"], 1.0, 0.0, x["S0"], x["z0"])
+    dO = _store(wl, np.random.default_rng(8).standard_normal(fwd["o"].shape) * 0.5)
+    ga = oracle.gla_backward(q, k, x["V"], x["G"], dO, 1.0, 0.0, x["S0"], x["z0"])
+    got = {}
+    for nm, src, wt, hl, dy, heads in (("q", "Q", "wq", "q_halo", ga["dq"], wl.Hq), ("k", "K", "wk", "k_halo", ga["dk"], wl.Hkv)):
+        dyr = _store(wl, dy)
+        ref = oracle.conv1d_backward(x[src], x[wt], dyr, x[hl], 1)
+        dx = torch.empty(x[src].shape, dtype=dt, device="cuda")
+        dw = torch.empty(x[wt].shape, dtype=torch.float32, device="cuda")
+        ws = lawcat.alloc_workspace(desc, lawcat.CALL_CONV1D_BACKWARD)
+        lawcat.conv1d_backward(desc, heads, H.dev(x[src], dt), H.dev(x[wt], dt), H.dev(x[hl], dt), H.dev(dyr, dt), dx, dw,
+                               None, ws)
+        torch.cuda.synchronize()
+        r = H.assert_close(H.host(dx), ref["dx"], wl, f"layer backward d{src}", 1)
+        scale = _abs_term_sum_dw(oracle, x[src], x[wt], x[hl], dyr, 1)
+        rw = (np.abs(H.host(dw) - ref["dw"]) / (2.0 ** -18 * scale + 1e-6)).max()
+        print(f"  d{src}: error / bar {r:.3f}; d{wt}: {rw:.3f}", flush=True)
+        assert rw <= 1.0, f"layer backward d{wt}: largest error is {rw:.3f} of its bar"

@@ -108,6 +108,9 @@ def test_backward_is_bit_identical(d):
     lawcat.gla_prefill(desc, q, k, v, g, S0, z0, o, den, torch.empty_like(S0), torch.empty_like(z0), ws)
     dO = torch.randn(o.shape, device="cuda", generator=torch.Generator("cuda").manual_seed(3)).to(dt)
     wb = lawcat.alloc_workspace(desc, lawcat.CALL_GLA_BACKWARD)
+    dconv = H.desc_for(wl, feature_map=1)
+    Qraw, wq = H.dev(x["Q"], dt), H.dev(x["wq"], dt)
+    wc = lawcat.alloc_workspace(dconv, lawcat.CALL_CONV1D_BACKWARD)
     first = None
     for it in range(RUNS):
         cur = {"dq": torch.empty_like(q), "dk": torch.empty_like(k), "dv": torch.empty_like(v), "dg": torch.empty_like(g),
@@ -115,6 +118,10 @@ def test_backward_is_bit_identical(d):
         wb.fill_(0xFF)     # NaN patterns: nothing is read before it is written
         lawcat.gla_backward(desc, q, k, v, g, den, dO, S0, z0, cur["dq"], cur["dk"], cur["dv"], cur["dg"], cur["dS0"],
                             cur["dz0"], wb)
+        # and the conv's adjoint on the query side (dw: per-strip partial sums added in strip order)
+        cur["dQ"], cur["dwq"] = torch.empty_like(q), torch.empty(wl.Hq, d, wl.W, device="cuda")
+        wc.fill_(0xFF)
+        lawcat.conv1d_backward(dconv, wl.Hq, Qraw, wq, None, cur["dq"], cur["dQ"], cur["dwq"], None, wc)
         torch.cuda.synchronize()
         for name, t in cur.items():
             assert torch.isfinite(t.float()).all(), f"d={d}: {name} of call {it} is not finite"

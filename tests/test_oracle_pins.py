@@ -410,6 +410,32 @@ def test_adjoint_of_the_conv_against_finite_differences(oracle, phi, halo):
     np.testing.assert_array_equal(oracle.conv1d_backward(x, imp, dy, None, 0)["dx"], dy)
 
 
+def test_adjoints_chained_give_the_gradient_of_the_whole_layer(oracle):
+    """gla_backward followed by conv1d_backward on (Q, wq, dq) and (K, wk, dk) is the gradient of layer_prefill:
+    against central finite differences of the forward oracle's whole layer (1 + ELU, grouped heads, halos, a start
+    state) with respect to the raw Q, K and both sets of conv weights."""
+    rng = np.random.default_rng(47)
+    B, T, Hq, Hkv, d, W = 1, 6, 4, 2, 3, 4
+    Q = _rand(rng, B, T, Hq, d)
+    K, V, G = (_rand(rng, B, T, Hkv, d) for _ in range(3))
+    wq, wk = _rand(rng, Hq, d, W), _rand(rng, Hkv, d, W)
+    qh, kh = _rand(rng, B, W - 1, Hq, d), _rand(rng, B, W - 1, Hkv, d)
+    S0, z0 = _rand(rng, B, Hkv, d, d), np.abs(_rand(rng, B, Hkv, d)) + 0.5
+    wgt = _rand(rng, B, T, Hq, d)
+
+    def loss():
+        r = oracle.layer_prefill(Q, K, V, G, wq, wk, feature_map=1, S0=S0, z0=z0, q_halo=qh, k_halo=kh)
+        return float((r["o"] * wgt).sum())
+
+    qd, kd = oracle.conv1d_causal(Q, wq, qh, 1), oracle.conv1d_causal(K, wk, kh, 1)
+    ga = oracle.gla_backward(qd, kd, V, G, wgt, 1.0, 0.0, S0, z0)
+    cq = oracle.conv1d_backward(Q, wq, ga["dq"], qh, 1)
+    ck = oracle.conv1d_backward(K, wk, ga["dk"], kh, 1)
+    for name, got, x in (("dQ", cq["dx"], Q), ("dK", ck["dx"], K), ("dwq", cq["dw"], wq), ("dwk", ck["dw"], wk),
+                         ("dq_halo", cq["dhalo"], qh)):
+        np.testing.assert_allclose(got, _fd(loss, x), rtol=5e-6, atol=5e-8, err_msg=name)
+
+
 def test_continuation_split_prefill_and_steps(oracle):
     """prefill(T) == prefill(T1) then prefill(T-T1) with carried (S, z, conv tails) == T single steps."""
     rng = np.random.default_rng(12)
