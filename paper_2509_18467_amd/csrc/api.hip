@@ -200,7 +200,7 @@ int lawcat_gla_backward(const lawcat_desc* desc, const void* q, const void* k, c
   p.q = q; p.k = k; p.v = v; p.g = gate_logits; p.den = den; p.dO = dO; p.S0 = S0; p.z0 = z0;
   p.dq = dq; p.dk = dk; p.dv = dv; p.dg = dgate_logits; p.dS0 = dS0; p.dz0 = dz0; p.workspace = workspace;
   p.B = desc->B; p.T = desc->T; p.Hq = desc->Hq; p.Hkv = desc->Hkv; p.d = desc->dk;
-  p.gate_scale = desc->gate_scale; p.eps = desc->eps; p.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
+  p.gate_scale = desc->gate_scale; p.bf16 = desc->dtype == LAWCAT_DTYPE_BF16;
   return hip_status(launch_gla_backward(p, static_cast<hipStream_t>(stream)));
 }
 

@@ -46,7 +46,7 @@ struct BwdArgs {
   float* gate_local; // [B,T,Hkv,D]: sum_h q (.) dq, then the suffix sum of the gate term within the segment
   float* gate_tot;   // [heads][nseg][D]: the segment's total, then the sum over all later segments
   int B, T, Hq, Hkv, group, seg_len, nseg;
-  float gate_scale, eps;
+  float gate_scale;
 };
 
 enum { kFwdContrib = 0, kFwdOut = 1, kRevContrib = 2, kRevOut = 3 };
@@ -541,7 +541,7 @@ hipError_t launch_gla_backward(const GlaBackwardParams& p, hipStream_t stream) {
   a.q = p.q; a.k = p.k; a.v = p.v; a.g = p.g; a.dO = p.dO; a.den = p.den; a.S0 = p.S0; a.z0 = p.z0;
   a.dq = p.dq; a.dk = p.dk; a.dv = p.dv; a.dg = p.dg; a.dS0 = p.dS0; a.dz0 = p.dz0;
   a.B = p.B; a.T = p.T; a.Hq = p.Hq; a.Hkv = p.Hkv; a.group = p.Hq / p.Hkv;
-  a.gate_scale = p.gate_scale; a.eps = p.eps;
+  a.gate_scale = p.gate_scale;
   gla_backward_plan(p.B, p.T, p.Hkv, &a.seg_len, &a.nseg);
   if (!gla_backward_supports(p.d, a.group)) return hipErrorInvalidValue;
   const size_t rows = (size_t)p.B * p.T;

@@ -36,7 +36,7 @@ struct GlaBackwardParams {
   float *dS0, *dz0;            // nullable
   void* workspace;
   int B, T, Hq, Hkv, d;
-  float gate_scale, eps;
+  float gate_scale;             // den already holds eps: the adjoint does not need it
   int bf16;
 };
 bool gla_backward_supports(int d, int group);

@@ -19,27 +19,39 @@ def _store(wl, a):
     return round_to_bf16(a) if wl.dtype == "bf16" else a
 
 
-@pytest.mark.parametrize("name,T,gate_scale,start", [
-    ("tiny", 256, 1.0, False), ("tiny", 77, 0.5, True),
-    ("llama1b_8k", 700, 1.0, True), ("llama1b_8k", 1500, 1.0, False), ("mistral7b_16k", 300, 1.0, True),
-    ("mistral7b_16k", 1100, 0.7, False),
+@pytest.mark.parametrize("name,T,gate_scale,start,eps", [
+    ("tiny", 256, 1.0, False, 0.0), ("tiny", 77, 0.5, True, 0.0),
+    ("llama1b_8k", 700, 1.0, True, 0.0), ("llama1b_8k", 1500, 1.0, False, 0.0), ("mistral7b_16k", 300, 1.0, True, 0.0),
+    ("mistral7b_16k", 1100, 0.7, False, 0.0), ("llama1b_8k", 900, 0.5, True, 0.3),
+    # every instantiation of the sweeps: 1, 2, 4, 8 query heads per kv head and the generic one (3, 16), both head dims,
+    # both storage types, more than one batch element
+    ("B2 Hq4 Hkv2 d64 bf16", 400, 1.0, True, 0.0), ("B1 Hq16 Hkv2 d64 bf16", 300, 1.0, False, 0.0),
+    ("B2 Hq6 Hkv2 d64 bf16", 200, 1.0, True, 0.0), ("B1 Hq16 Hkv1 d64 fp32", 150, 1.0, True, 0.0),
+    ("B1 Hq2 Hkv2 d128 bf16", 300, 1.0, True, 0.0), ("B2 Hq4 Hkv2 d128 fp32", 200, 0.8, False, 0.0),
+    ("B1 Hq8 Hkv1 d128 bf16", 260, 1.0, True, 0.0), ("B1 Hq3 Hkv1 d128 bf16", 100, 1.0, False, 0.0),
+    ("B1 Hq4 Hkv1 d64 fp32", 2500, 1.0, True, 0.0),
 ])
-def test_gla_backward(oracle, name, T, gate_scale, start):
-    wl = WORKLOADS[name].with_T(T)
+def test_gla_backward(oracle, name, T, gate_scale, start, eps):
+    if name in WORKLOADS:
+        wl = WORKLOADS[name].with_T(T)
+    else:
+        f = dict((k.rstrip("0123456789"), k) for k in name.split())
+        wl = Workload(name, B=int(f["B"][1:]), T=T, Hq=int(f["Hq"][2:]), Hkv=int(f["Hkv"][3:]), d=int(f["d"][1:]),
+                      dtype=name.split()[-1])
     x = make_inputs(wl, seed=11, state=start)
-    print("gla_backward", wl, "gate_scale", gate_scale, "start state", start, flush=True)
+    print("gla_backward", wl, "gate_scale", gate_scale, "start state", start, "eps", eps, flush=True)
     # positive features, as phi = 1 + ELU gives them
     q = _store(wl, oracle.conv1d_causal(x["Q"], x["wq"], None, 1))
     k = _store(wl, oracle.conv1d_causal(x["K"], x["wk"], None, 1))
     v, g = x["V"], x["G"]
     S0, z0 = x.get("S0"), x.get("z0")
-    fwd = oracle.gla_prefill(q, k, v, g, gate_scale, 0.0, S0, z0)
+    fwd = oracle.gla_prefill(q, k, v, g, gate_scale, eps, S0, z0)
     den = fwd["den"].astype(np.float32)
     dO = _store(wl, np.random.default_rng(5).standard_normal(fwd["o"].shape) * 0.5)
-    ref = oracle.gla_backward(q, k, v, g, dO, gate_scale, 0.0, S0, z0)
+    ref = oracle.gla_backward(q, k, v, g, dO, gate_scale, eps, S0, z0)
 
     dt = H.tdtype(wl)
-    desc = H.desc_for(wl, gate_scale=gate_scale)
+    desc = H.desc_for(wl, gate_scale=gate_scale, eps=eps)
     dq_, dk_, dv_, dg_ = (H.dev(a, dt) for a in (q, k, v, g))
     outs = {"dq": torch.empty_like(dq_), "dk": torch.empty_like(dk_), "dv": torch.empty_like(dv_), "dg": torch.empty_like(dg_)}
     dS0 = torch.empty(wl.B, wl.Hkv, wl.d, wl.d, device="cuda")
