@@ -203,7 +203,7 @@ __global__ void __launch_bounds__(256) bwd_pass_kernel(const BwdArgs a) {
     for (int i = 0; i < KV; ++i) {
       const int idx = i * 256 + tid;
       if (idx < n * D) {
-        s_al[idx] = a.gate_scale == 1.0f ? 1.f / (1.f + expf(-pg[i])) : expf(a.gate_scale * log_sigmoid(pg[i]));
+        s_al[idx] = a.gate_scale == 1.0f ? __frcp_rn(1.f + __expf(-pg[i])) : expf(a.gate_scale * log_sigmoid(pg[i]));
         if (MODE != kRevContrib) {
           s_k[idx] = pk[i];
           s_v[idx] = pv_[i];
@@ -222,7 +222,7 @@ __global__ void __launch_bounds__(256) bwd_pass_kernel(const BwdArgs a) {
             const int el = e * 256 + tid;
             if (el < gD) {
               s_q[tl * gD + el] = pq[tl * EI + e];
-              s_dn[tl * gD + el] = pdo[tl * EI + e] / pden[tl * EI + e];     // dnum = dO / den
+              s_dn[tl * gD + el] = pdo[tl * EI + e] * __frcp_rn(pden[tl * EI + e]);     // dnum = dO / den
             }
           }
         }
