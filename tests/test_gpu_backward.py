@@ -150,3 +150,67 @@ def test_layer_backward_as_a_chain_of_calls(oracle, name, T):
         rw = (np.abs(H.host(dw) - ref["dw"]) / (2.0 ** -18 * scale + 1e-6)).max()
         print(f"  d{src}: error / bar {r:.3f}; d{wt}: {rw:.3f}", flush=True)
         assert rw <= 1.0, f"layer backward d{wt}: largest error is {rw:.3f} of its bar"
+
+
+@pytest.mark.parametrize("T", [1, 7, 8, 9, 65])
+@pytest.mark.parametrize("gates", ["closed", "open", "mixed"])
+def test_gla_backward_short_sequences_and_saturated_gates(oracle, T, gates):
+    """Sequences shorter than, equal to and just longer than a staged block of 8 tokens and a 64-token segment,
+    with gate logits at -30 (nothing is carried: alpha ~ 1e-13), +30 (nothing decays) or a mix of both with
+    ordinary ones.  fp32 storage: the backward has no floor on the decay, so the fp32 bar holds throughout."""
+    wl = Workload(f"edge T{T} {gates}", B=2, T=T, Hq=4, Hkv=2, d=64, dtype="fp32")
+    x = make_inputs(wl, seed=31, state=True)
+    rng = np.random.default_rng(32)
+    g = x["G"].copy()
+    if gates == "closed":
+        g[:] = -30.0
+    elif gates == "open":
+        g[:] = 30.0
+    else:
+        pick = rng.random(g.shape)
+        g[pick < 0.1] = -30.0
+        g[pick > 0.9] = 30.0
+    q = np.abs(x["Q"]).astype(np.float32) + 0.1
+    k = np.abs(x["K"]).astype(np.float32) + 0.1
+    v, S0, z0 = x["V"], x["S0"], np.abs(x["z0"]) + 0.5
+    fwd = oracle.gla_prefill(q, k, v, g, 1.0, 0.0, S0, z0)
+    dO = (rng.standard_normal(fwd["o"].shape) * 0.5).astype(np.float32)
+    ref = oracle.gla_backward(q, k, v, g, dO, 1.0, 0.0, S0, z0)
+    desc = H.desc_for(wl)
+    tq, tk, tv, tg = (H.dev(a) for a in (q, k, v, g))
+    outs = {"dq": torch.empty_like(tq), "dk": torch.empty_like(tk), "dv": torch.empty_like(tv), "dg": torch.empty_like(tg),
+            "dS0": torch.empty(wl.B, wl.Hkv, wl.d, wl.d, device="cuda"), "dz0": torch.empty(wl.B, wl.Hkv, wl.d, device="cuda")}
+    ws = lawcat.alloc_workspace(desc, lawcat.CALL_GLA_BACKWARD)
+    lawcat.gla_backward(desc, tq, tk, tv, tg, H.dev(fwd["den"].astype(np.float32)), H.dev(dO), H.dev(S0), H.dev(z0),
+                        outs["dq"], outs["dk"], outs["dv"], outs["dg"], outs["dS0"], outs["dz0"], ws)
+    torch.cuda.synchronize()
+    for n, t in outs.items():
+        H.assert_close(H.host(t), ref[n], wl, f"gla_backward {n} (T={T}, gates {gates})")
+
+
+@pytest.mark.parametrize("name,T", [("llama1b_8k", 1300), ("mistral7b_16k", 600)])
+def test_backward_after_the_forward_call(oracle, name, T):
+    """As a caller uses the pair: lawcat_gla_prefill's own den_out (matrix-core path, about 1e-3 off the oracle's)
+    goes into lawcat_gla_backward.  A relative error of den scales dnum and dden of that token and head alike, so it
+    arrives in the gradients as the same relative error: the bars of the backward alone still hold."""
+    wl = WORKLOADS[name].with_T(T)
+    x = make_inputs(wl, seed=11, state=True)
+    print("forward + backward", wl, flush=True)
+    q = _store(wl, oracle.conv1d_causal(x["Q"], x["wq"], None, 1))
+    k = _store(wl, oracle.conv1d_causal(x["K"], x["wk"], None, 1))
+    v, g, S0, z0 = x["V"], x["G"], x["S0"], x["z0"]
+    dt = H.tdtype(wl)
+    desc = H.desc_for(wl)
+    tq, tk, tv, tg = (H.dev(a, dt) for a in (q, k, v, g))
+    o, den = torch.empty_like(tq), torch.empty(wl.B, wl.T, wl.Hq, device="cuda")
+    lawcat.gla_prefill(desc, tq, tk, tv, tg, H.dev(S0), H.dev(z0), o, den, torch.empty(wl.B, wl.Hkv, wl.d, wl.d, device="cuda"),
+                       torch.empty(wl.B, wl.Hkv, wl.d, device="cuda"), lawcat.alloc_workspace(desc, lawcat.CALL_GLA_PREFILL))
+    dO = _store(wl, np.random.default_rng(5).standard_normal(tuple(o.shape)) * 0.5)
+    ref = oracle.gla_backward(q, k, v, g, dO, 1.0, 0.0, S0, z0)
+    outs = {"dq": torch.empty_like(tq), "dk": torch.empty_like(tk), "dv": torch.empty_like(tv), "dg": torch.empty_like(tg)}
+    lawcat.gla_backward(desc, tq, tk, tv, tg, den, H.dev(dO, dt), H.dev(S0), H.dev(z0), outs["dq"], outs["dk"], outs["dv"],
+                        outs["dg"], None, None, lawcat.alloc_workspace(desc, lawcat.CALL_GLA_BACKWARD))
+    torch.cuda.synchronize()
+    for n, t in outs.items():
+        r = H.assert_close(H.host(t), ref[n], wl, f"forward + backward {n}", 1)
+        print(f"  {n}: error / bar {r:.3f}", flush=True)
