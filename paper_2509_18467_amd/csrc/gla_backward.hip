@@ -437,16 +437,24 @@ __global__ void __launch_bounds__(256) bwd_scan_kernel(float* __restrict__ slots
   }
 }
 
-// gate_tot[seg] <- sum of the totals of all later segments.  grid (heads), D threads.
+// gate_tot[seg] <- sum of the totals of all later segments.  grid (heads), D threads.  The loads do not depend
+// on the running sum: eight are issued at a time.
 template <int D>
 __global__ void bwd_gate_suffix_kernel(float* __restrict__ tot, int nseg) {
   const int bh = blockIdx.x, c = threadIdx.x;
   float* p = tot + (size_t)bh * nseg * D + c;
   float acc = 0.f;
-  for (int s = nseg - 1; s >= 0; --s) {
-    const float t = p[(size_t)s * D];
-    p[(size_t)s * D] = acc;
-    acc += t;
+  constexpr int U = 8;
+  for (int s1 = nseg; s1 > 0; s1 -= U) {
+    float t[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) t[u] = s1 - 1 - u >= 0 ? p[(size_t)(s1 - 1 - u) * D] : 0.f;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (s1 - 1 - u >= 0) {
+        p[(size_t)(s1 - 1 - u) * D] = acc;
+        acc += t[u];
+      }
   }
 }
 
