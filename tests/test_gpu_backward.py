@@ -88,6 +88,8 @@ def _abs_term_sum_dw(oracle, x, w, halo, dy, phi):
     ("tiny", 1, 200, 1, 1, False), ("tiny", 1, 2, 4, 1, True),
     ("llama1b_8k", 1, 1500, 4, 1, True), ("llama1b_8k", 2, 333, 4, 1, False), ("mistral7b_16k", 1, 700, 4, 1, True),
     ("mistral7b_16k", 1, 129, 3, 0, True),
+    # full size, the shape the benchmark's side op times
+    ("llama1b_32k", 1, 32768, 4, 1, True), ("mistral7b_16k", 1, 16384, 4, 1, True),
 ])
 def test_conv1d_backward(oracle, name, B, T, W, phi, halo):
     import dataclasses
@@ -213,4 +215,32 @@ def test_backward_after_the_forward_call(oracle, name, T):
     torch.cuda.synchronize()
     for n, t in outs.items():
         r = H.assert_close(H.host(t), ref[n], wl, f"forward + backward {n}", 1)
+        print(f"  {n}: error / bar {r:.3f}", flush=True)
+
+
+@pytest.mark.parametrize("name", ["llama1b_32k", "mistral7b_16k"])
+def test_gla_backward_full_size(oracle, name):
+    """The two headline shapes at full length, in the launch plan the benchmark's side op times (128 / 64
+    segments per kv head), every element of every gradient against the oracle (10-20 s of host time each)."""
+    wl = WORKLOADS[name]
+    x = make_inputs(wl, seed=13, state=True)
+    print("gla_backward full size", wl, flush=True)
+    q = _store(wl, oracle.conv1d_causal(x["Q"], x["wq"], None, 1))
+    k = _store(wl, oracle.conv1d_causal(x["K"], x["wk"], None, 1))
+    v, g, S0, z0 = x["V"], x["G"], x["S0"], x["z0"]
+    fwd = oracle.gla_prefill(q, k, v, g, 1.0, 0.0, S0, z0)
+    den = fwd["den"].astype(np.float32)
+    dO = _store(wl, np.random.default_rng(5).standard_normal(fwd["o"].shape) * 0.5)
+    del fwd
+    ref = oracle.gla_backward(q, k, v, g, dO, 1.0, 0.0, S0, z0)
+    dt = H.tdtype(wl)
+    desc = H.desc_for(wl)
+    tq, tk, tv, tg = (H.dev(a, dt) for a in (q, k, v, g))
+    outs = {"dq": torch.empty_like(tq), "dk": torch.empty_like(tk), "dv": torch.empty_like(tv), "dg": torch.empty_like(tg),
+            "dS0": torch.empty(wl.B, wl.Hkv, wl.d, wl.d, device="cuda"), "dz0": torch.empty(wl.B, wl.Hkv, wl.d, device="cuda")}
+    lawcat.gla_backward(desc, tq, tk, tv, tg, H.dev(den), H.dev(dO, dt), H.dev(S0), H.dev(z0), outs["dq"], outs["dk"],
+                        outs["dv"], outs["dg"], outs["dS0"], outs["dz0"], lawcat.alloc_workspace(desc, lawcat.CALL_GLA_BACKWARD))
+    torch.cuda.synchronize()
+    for n, t in outs.items():
+        r = H.assert_close(H.host(t), ref[n], wl, f"gla_backward full size {n}", 1 if n in ("dq", "dk", "dv", "dg") else 0)
         print(f"  {n}: error / bar {r:.3f}", flush=True)
