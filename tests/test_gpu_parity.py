@@ -78,11 +78,26 @@ def test_conv1d_feature(oracle, dtype, T, Hh, Hkv, d, W, phi, halo):
         assert np.array_equal(tail, full[:, -(W - 1):]), "tail rows must be bit-exact copies"
 
 
+@pytest.mark.parametrize("name", ["llama1b_32k", "mistral7b_16k"])
+def test_conv1d_feature_full_size(oracle, name):
+    """The query side of the two headline shapes at full length (the grid the benchmark's side op times: one round
+    of workgroups over the chip), every element against the oracle."""
+    wl = WORKLOADS[name]
+    _say("conv + linear feature map, full size", wl)
+    xin = make_inputs(wl, seed=17, halo=True)
+    wf = make_feature_weights(wl, seed=17)
+    y, tail = H.run_conv_feature(wl, xin["Q"], xin["wq"], wf, xin["q_halo"], 1)
+    ref = oracle.feature_linear(oracle.conv1d_causal(xin["Q"], xin["wq"], xin["q_halo"], 0), wf, 1)
+    r = H.assert_close(y, ref, wl, "conv + feature y, full size")
+    _say("  error / bar", f"{r:.3f}")
+
+
 # ------------------------------------------------------------------ gate logits from the layer input (section 4.2)
 @pytest.mark.parametrize("dtype,B,T,Hkv,d,dm,rank,bias", [
     ("bf16", 1, 300, 8, 64, 2048, 32, True), ("bf16", 2, 77, 8, 128, 4096, 32, False), ("bf16", 1, 1, 2, 64, 128, 32, True),
     ("bf16", 1, 8192, 8, 64, 2048, 32, True), ("bf16", 1, 4096, 8, 128, 4096, 32, True),
     ("bf16", 1, 16411, 8, 64, 2048, 32, True), ("bf16", 2, 8200, 8, 128, 4096, 32, False),   # 32 tokens per workgroup
+    ("bf16", 1, 32768, 8, 64, 2048, 32, True), ("bf16", 1, 16384, 8, 128, 4096, 32, True),   # the headline shapes, full length
     ("bf16", 3, 50, 3, 64, 256, 16, True), ("bf16", 1, 40, 2, 64, 264, 8, False),
     ("fp32", 2, 33, 2, 64, 256, 32, True), ("fp32", 1, 20, 2, 128, 512, 16, False),
 ])
