@@ -433,7 +433,9 @@ def test_layer_prefill_with_linear_feature_map(oracle, name, T, phi, extras):
 @pytest.mark.parametrize("one_launch", [False, True])
 @pytest.mark.parametrize("name,lengths", [("tiny", (5, 130, 1, 64)), ("llama1b_8k", (700, 64, 1500, 1, 333)),
                                           ("mistral7b_16k", (257, 1024, 16)), ("llama1b_8k", (4000, 130, 2500)),
-                                          ("llama1b_8k", tuple(37 + 11 * i for i in range(70)))])
+                                          ("llama1b_8k", tuple(37 + 11 * i for i in range(70))),
+                                          # the packed batch the benchmark's side op times: 24 sequences, 32 768 tokens
+                                          ("llama1b_8k", (4096, 2048, 1024, 512, 256, 256) * 4)])
 def test_layer_prefill_varlen(oracle, name, lengths, one_launch):
     """lawcat_layer_prefill_varlen: every sequence of the packed batch equals the oracle run on that sequence alone
     (its own start state, conv halo, final state and conv tails) -- as one call per sequence, and as one set of
