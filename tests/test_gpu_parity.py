@@ -577,6 +577,37 @@ def test_prefill_then_decode_steps(oracle, name, T, n):
     H.assert_close(got["z"], ref["z"], wl, "decode z")
 
 
+@pytest.mark.parametrize("d,n", [(64, 3), (128, 2)])
+def test_decode_steps_for_a_batch_of_256_sequences(oracle, d, n):
+    """lawcat_gla_step on a batch of 256 sequences (the shape the benchmark's side op times), a few steps in a row
+    from a random start state, and the same tokens through one lawcat_gla_steps call: every sequence and head
+    against the oracle's recurrence."""
+    wl = Workload("decode_b256", B=256, T=n, Hq=32, Hkv=8, d=d)
+    x = make_inputs(wl, seed=29, state=True)
+    dt = H.tdtype(wl)
+    q = _store(wl, np.abs(x["Q"]) + 0.05)
+    k = _store(wl, np.abs(x["K"]) + 0.05)
+    ref = oracle.gla_prefill(q, k, x["V"], x["G"], 1.0, 0.0, x["S0"], x["z0"])
+    d1 = H.desc_for(wl.with_T(1))
+    tq, tk, tv, tg = (H.dev(a, dt) for a in (q, k, x["V"], x["G"]))
+    S, z = H.dev(x["S0"]), H.dev(x["z0"])
+    o = torch.empty(wl.B, n, wl.Hq, d, dtype=dt, device="cuda")
+    for t in range(n):
+        ot = torch.empty(wl.B, wl.Hq, d, dtype=dt, device="cuda")
+        lawcat.gla_step(d1, tq[:, t].contiguous(), tk[:, t].contiguous(), tv[:, t].contiguous(), tg[:, t].contiguous(), S, z, ot)
+        o[:, t] = ot
+    torch.cuda.synchronize()
+    for nm, got in (("o", o), ("S", S), ("z", z)):
+        r = H.assert_close(H.host(got), ref[nm], wl, f"batched decode step {nm}")
+        _say(f"  {nm}: error / bar {r:.3f}")
+    S2, z2 = H.dev(x["S0"]), H.dev(x["z0"])
+    o2 = torch.empty_like(o)
+    lawcat.gla_steps(H.desc_for(wl), tq, tk, tv, tg, S2, z2, o2)
+    torch.cuda.synchronize()
+    for nm, got in (("o", o2), ("S", S2), ("z", z2)):
+        H.assert_close(H.host(got), ref[nm], wl, f"batched decode block {nm}")
+
+
 @pytest.mark.parametrize("phi", [1, 0])
 def test_stress_128k_then_256_steps(oracle, phi):
     """Mistral-7B shape at T = 131072, every head against the oracle, then 256 decode steps from the returned
