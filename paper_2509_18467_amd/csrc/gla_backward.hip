@@ -18,7 +18,6 @@
 // through shuffles and LDS in a fixed order (no atomics: repeated calls agree bit for bit).  Tokens are staged
 // through LDS in blocks of up to 8, the next block's loads in flight while the current one is worked on.
 // A first version: correct and segment-parallel, several times the forward's time.
-#include <mutex>
 
 #include "kernels.h"
 
