@@ -4,7 +4,8 @@
  * The library implements the prefill forward of LAWCAT's attention replacement
  * (arXiv 2509.18467, section 4): a causal depthwise Conv1D across tokens on the
  * queries and on the keys (section 4.1) feeding gated linear attention with the
- * normalization term kept (section 4.2).
+ * normalization term kept (section 4.2); beside it the feature map with its linear layer,
+ * the low-rank gate projection, decode steps and a first backward of the layer.
  *
  * Conventions shared by every call
  * --------------------------------
@@ -30,7 +31,7 @@
  *    below -9.0 at gate_scale 1), so that the reciprocal decay products inside an 8-token half chunk stay below
  *    2^104.  What is lost is a factor that is already below 1.3e-4 of what it multiplies, i.e. under the bf16
  *    resolution of the operands; logits of -30 everywhere, +30 everywhere and gate_scale 0 .. 16 meet the same
- *    tolerance as ordinary gates.  fp32 storage, lawcat_gla_step and lawcat_gla_steps do not clamp.
+ *    tolerance as ordinary gates.  fp32 storage, lawcat_gla_step, lawcat_gla_steps and lawcat_gla_backward do not clamp.
  *  - Return value: LAWCAT_OK or a negative lawcat_status.  All argument checks run on
  *    the host before anything is enqueued; after an error the outputs are unspecified.
  *    A zero denominator is not an error: IEEE inf/nan is returned as the last equation
