@@ -174,7 +174,7 @@ LAWCAT_API int lawcat_gla_backward(const lawcat_desc* desc, const void* q, const
  *   x, w, halo as lawcat_conv1d_causal took them; dy, dx [B,T,n_heads,d]; dhalo [B,W-1,n_heads,d]; dw [n_heads,d,W].
  * Workspace: LAWCAT_CALL_CONV1D_BACKWARD (partial sums of dw per 64-token strip, added in a fixed order: repeated
  * calls agree bit for bit).  A layer's backward is lawcat_gla_backward followed by this call on (Q, wq, dq) and on
- * (K, wk, dk).
+ * (K, wk, dk).  B above 65535 or T above 65535 * 64 is LAWCAT_E_UNSUPPORTED (grid limits).
  */
 LAWCAT_API int lawcat_conv1d_backward(const lawcat_desc* desc, int n_heads, const void* x, const void* w, const void* halo,
                            const void* dy, void* dx, float* dw, void* dhalo, void* workspace,
